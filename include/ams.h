@@ -1,0 +1,129 @@
+/*
+ * ams.h -- C ABI of the MI355X (gfx950) AMS-Quant weight-only quantized Linear.
+ *
+ * The library implements the decode-time Linear of AMS-Quant (arxiv 2510.16045):
+ * weights are stored in a non-integer bit-width floating-point format in which a
+ * group of k consecutive input-channel weights shares its last mantissa bit
+ * (Sec. 3.1), are restored to fp16 on the fly by bit operations (Sec. 3.2) and
+ * multiplied by a skinny fp16 activation matrix (Sec. 3.3, Sec. 4.2).
+ *
+ * Conventions for every entry point
+ *   - Return value: 0 (AMS_OK) or a negative AMS_ERR_* code; nothing throws or aborts.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory of the current device.  The caller owns every buffer.
+ *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream); they never synchronize and never allocate.
+ *   - fp16 values travel as uint16_t bit patterns (IEEE binary16).
+ *   - W is [N, K]: N output channels (rows), K input channels; one fp16 scale per row.
+ *   - A "code" is one weight's mini-float [S | E(2) | M(m)] with exponent bias 1,
+ *     subnormals, and no inf/NaN (Sec. 2.2, Table 1): 6 bits for e2m3, 5 for e2m2.
+ */
+#ifndef AMS_H_
+#define AMS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Formats (abstract; Sec. 3.2, Sec. 3.3 item 1). */
+enum {
+  AMS_FMT_FP533_E2M3 = 0, /* e2m3 codes, groups of 3 along K share the mantissa LSB: 16/3 bits per weight */
+  AMS_FMT_FP425_E2M2 = 1  /* e2m2 codes, groups of 4 along K share the mantissa LSB: 4.25 bits per weight */
+};
+
+enum {
+  AMS_OK = 0,
+  AMS_ERR_FORMAT = -1,    /* unknown fmt */
+  AMS_ERR_SHAPE = -2,     /* N, K, M or a leading dimension out of range */
+  AMS_ERR_NULL = -3,      /* a required pointer is NULL */
+  AMS_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned */
+  AMS_ERR_NONFINITE = -5, /* a weight is inf or NaN */
+  AMS_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch (see hipGetLastError) */
+  AMS_ERR_DEVICE = -7     /* the current device is not a gfx950 GPU */
+};
+
+#define AMS_MAX_M 32 /* largest activation batch of ams_linear / ams_fp16_linear (Table 3: batch 1..32) */
+
+int ams_version(void);
+const char* ams_strerror(int code);
+
+/* Group size k of the format (3 or 4) and bits of one code (6 or 5); 0 for an unknown fmt. */
+int ams_group_size(int fmt);
+int ams_code_bits(int fmt);
+
+/*
+ * Size in bytes of the packed weight buffer in this library's gfx950 layout
+ * (what ams_pack writes and ams_dequant / ams_linear read).  The layout is opaque:
+ * 16-row x 96-weight (FP5.33) or 16-row x 128-weight (FP4.25) records of 64
+ * 16-byte lane chunks, so N is padded to a multiple of 16 and K to a multiple of
+ * 96 / 128; padding holds zero codes.
+ */
+int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
+
+/*
+ * Size in bytes of the paper's own packing: one uint16 per 3 weights for FP5.33
+ * (Sec. 3.3 item 1), 17 uint16 per 64 weights for FP4.25 (Sec. 3.2).  This is the
+ * "algorithmic" byte count used when bandwidth is reported.
+ */
+int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
+
+/*
+ * Offline quantizer + packer (Sec. 3.1; Sec. 3.3 stage 1).  All pointers are host.
+ *   W_fp16      [N, ldw] fp16 weights, row n at W_fp16 + n*ldw, ldw >= K
+ *   packed      out, ams_packed_bytes() bytes
+ *   scales_fp16 out, [N] fp16: s_n = fp16(max_k|W[n,k]| / Fmax) (Eq. 1), 1.0 for a row
+ *               whose scale would be zero
+ *   codes       out or NULL, [N, K] one byte per weight: the final code, whose last
+ *               bit is the group's shared bit
+ * Per row: RTN of W/s to the nearest code (ties to the even code, saturating);
+ * then per group of k consecutive weights along K both values of the shared last
+ * bit are tried and the one with the smaller fp64 sum of squared errors against
+ * the original weights is kept (a tie keeps 0; a short last group counts only its
+ * real members).  Deterministic.  Errors: FORMAT, SHAPE, NULL, NONFINITE.
+ */
+int ams_pack(int fmt, const uint16_t* W_fp16, int64_t N, int64_t K, int64_t ldw, void* packed,
+             uint16_t* scales_fp16, uint8_t* codes);
+
+/*
+ * Pack codes that were produced elsewhere (e.g. read from the paper's layout) into
+ * the gfx950 layout.  codes [N, K] as written by ams_pack; within a group all last
+ * bits must agree (else AMS_ERR_SHAPE).  Host pointers.
+ */
+int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* packed);
+
+/* Inverse of the layout step: packed (host) -> codes [N, K] (host).  Debug / tests. */
+int ams_unpack_host(int fmt, const void* packed, int64_t N, int64_t K, uint8_t* codes);
+
+/*
+ * Bit-level restoration (Sec. 3.2, Sec. 3.3 stages 2-3) of a whole packed matrix.
+ *   W_packed device, 16-byte aligned;  scales device [N] fp16 (may be NULL if !scaled)
+ *   W_out    device [N, K] fp16 row-major, logical k order
+ *   scaled=0: the code's own value (exact);  scaled=1: fp16_RNE(value * s_n) (Eq. 2)
+ */
+int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t* W_out, int64_t N, int64_t K,
+                int scaled, void* stream);
+
+/*
+ * The quantized Linear (Sec. 3.3; Sec. 4.2 "GEMV-like operations"):
+ *   Y[m, n] = fp16( sum_k value(code[n,k]) * s_n * X[m, k] ),  fp32 accumulation.
+ *   W_packed device (ams_pack layout), scales device [N] fp16,
+ *   X device [M, K] fp16 row-major, Y device [M, N] fp16 row-major, 1 <= M <= AMS_MAX_M.
+ * All four pointers must be 16-byte aligned.  X and Y must not alias.
+ */
+int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
+               int64_t K, int fmt, void* stream);
+
+/*
+ * The unquantized fp16 Linear Y = X W^T (the W16A16 baseline of Sec. 4.2) written for
+ * the same GPU, used as the denominator of the reported speed-ups.
+ *   W device [N, K] fp16 row-major (K a multiple of 8), X [M, K], Y [M, N], 1 <= M <= AMS_MAX_M.
+ */
+int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMS_H_ */

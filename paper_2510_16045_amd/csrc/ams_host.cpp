@@ -1,0 +1,330 @@
+// Host side of the AMS-Quant library: the offline quantizer (Sec. 3.1) and the
+// packer into the gfx950 layout (Sec. 3.3 stage 1), plus the size queries.
+// Compiled with -ffp-contract=off: the squared-error comparison of the adaptive
+// search is specified as plain IEEE fp64 operations in member order.
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "../../include/ams.h"
+#include "ams_layout.h"
+
+namespace {
+
+using ams::FormatInfo;
+
+// ---- binary16 <-> double -------------------------------------------------
+inline double half_to_double(uint16_t h) {
+  int s = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0)
+    v = std::ldexp((double)m, -24);
+  else if (e == 31)
+    v = m ? NAN : INFINITY;
+  else
+    v = std::ldexp((double)(1024 + m), e - 25);
+  return s ? -v : v;
+}
+
+// round-to-nearest-even conversion of a finite non-negative double
+inline uint16_t double_to_half_bits(double a) {
+  if (a == 0) return 0;
+  int ex;
+  (void)std::frexp(a, &ex);  // a = f * 2^ex, f in [0.5, 1)
+  int e = ex - 1;            // a = 1.xxx * 2^e
+  if (e < -14) e = -14;      // subnormal quantum 2^-24
+  double q = std::nearbyint(std::ldexp(a, 10 - e));  // integer significand, RNE
+  if (q >= 2048) {           // rounded up into the next binade
+    q = 1024;
+    e += 1;
+  }
+  if (e > 15) return 0x7C00;  // overflow to inf (cannot happen for absmax / Fmax)
+  if (q < 1024) return (uint16_t)q;  // subnormal (or zero)
+  return (uint16_t)(((e + 15) << 10) | ((int)q - 1024));
+}
+
+// ---- Sec. 2.2: magnitude of a magnitude code, bias 1 ----------------------
+inline double magnitude(int mag_code, int mbits) {
+  int e = mag_code >> mbits, m = mag_code & ((1 << mbits) - 1);
+  if (e == 0) return std::ldexp((double)m, -mbits);
+  return std::ldexp((double)((1 << mbits) + m), e - 1 - mbits);
+}
+
+// ---- Eq. 1: Round(t) = nearest magnitude, ties to the even code, saturating
+inline int rtn_magnitude_code(double a, int mbits) {
+  // the grid is uniform with step 2^-m below 2, 2^(1-m) in [2,4), 2^(2-m) from 4 on
+  const int one = 1 << mbits;  // code of 1.0
+  int sh = a < 2.0 ? 0 : (a < 4.0 ? 1 : 2);
+  double r = std::nearbyint(std::ldexp(a, mbits - sh));  // round-half-even on the grid
+  int code;
+  if (sh == 0)
+    code = (int)r;             // 0 .. 2*one
+  else if (sh == 1)
+    code = one + (int)r;       // r in [one, 2*one]
+  else {
+    if (r > 4.0 * one) r = 4.0 * one;  // keep the cast in range for huge inputs
+    code = 2 * one + (int)r;   // r >= one
+  }
+  return std::min(code, 4 * one - 1);
+}
+
+struct RowQuant {
+  int mbits, group;
+  double fmax;
+};
+
+// Quantize one row: scale (Eq. 1), RTN, adaptive search of each group's shared bit.
+// Returns false on inf/NaN.
+bool quantize_row(const RowQuant& q, const uint16_t* w, int64_t K, uint8_t* codes, uint16_t* scale_out) {
+  double absmax = 0;
+  for (int64_t k = 0; k < K; k++) {
+    if (((w[k] >> 10) & 31) == 31) return false;
+    absmax = std::max(absmax, std::fabs(half_to_double(w[k])));
+  }
+  uint16_t sb = double_to_half_bits(absmax / q.fmax);
+  if (sb == 0) sb = 0x3C00;  // a zero scale would not decode: use 1.0
+  *scale_out = sb;
+  const double s = half_to_double(sb);
+  const int sign_shift = 2 + q.mbits;
+  for (int64_t k0 = 0; k0 < K; k0 += q.group) {
+    const int n = (int)std::min<int64_t>(q.group, K - k0);
+    int c[4];
+    double sse0 = 0, sse1 = 0;
+    for (int i = 0; i < n; i++) {
+      const double wv = half_to_double(w[k0 + i]);
+      const int mc = rtn_magnitude_code(std::fabs(wv / s), q.mbits);
+      c[i] = mc | ((wv < 0 ? 1 : 0) << sign_shift);
+      const double sg = wv < 0 ? -1.0 : 1.0;
+      const double d0 = sg * magnitude(mc & ~1, q.mbits) * s - wv;  // Eq. 2 with last bit 0
+      const double d1 = sg * magnitude(mc | 1, q.mbits) * s - wv;   // ... with last bit 1
+      sse0 = sse0 + d0 * d0;
+      sse1 = sse1 + d1 * d1;
+    }
+    const int m0 = sse1 < sse0 ? 1 : 0;  // a tie keeps 0
+    for (int i = 0; i < n; i++) codes[k0 + i] = (uint8_t)((c[i] & ~1) | m0);
+  }
+  return true;
+}
+
+// ---- layout ---------------------------------------------------------------
+// Writes the records of one strip.  codes: 16 rows of K bytes (row pointer NULL = padding row).
+void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], int64_t K, uint8_t* strip_out) {
+  const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
+  for (int64_t j = 0; j < n_rec; j++) {
+    uint8_t* rec = strip_out + j * fi.rec_bytes;
+    for (int l = 0; l < ams::kLanes; l++) {
+      const uint8_t* row = rows[l & 15];
+      const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
+      auto code_at = [&](int i) -> int { return (row && kbase + i < K) ? row[kbase + i] : 0; };
+      uint32_t words[4];
+      uint32_t shared_byte = 0;
+      for (int d = 0; d < 4; d++) {
+        uint32_t half[2];
+        for (int h = 0; h < 2; h++) {
+          if (fmt == AMS_FMT_FP425_E2M2) {
+            int rem[4], sh = 0;
+            for (int i = 0; i < 4; i++) {
+              int c = code_at(8 * d + 4 * h + i);
+              rem[i] = c >> 1;
+              sh |= c & 1;  // members agree (checked by the caller); padding is 0
+            }
+            auto sg = [&](int i) { return (uint32_t)(rem[i] >> 3); };
+            auto mg = [&](int i) { return (uint32_t)(rem[i] & 7); };
+            half[h] = sg(0) << 15 | sg(2) << 14 | sg(3) << 13 | sg(1) << 12 | mg(0) << 9 | mg(1) << 6 | mg(2) << 3 | mg(3);
+            shared_byte |= (uint32_t)sh << (4 * h + d);
+          } else {
+            int rem[3], sh = 0;
+            for (int i = 0; i < 3; i++) {
+              int c = code_at(6 * d + 3 * h + i);
+              rem[i] = c >> 1;
+              sh |= c & 1;
+            }
+            auto sg = [&](int i) { return (uint32_t)(rem[i] >> 4); };
+            auto mg = [&](int i) { return (uint32_t)(rem[i] & 15); };
+            half[h] = sg(0) << 15 | sg(1) << 14 | sg(2) << 13 | (uint32_t)sh << 12 | mg(0) << 8 | mg(1) << 4 | mg(2);
+          }
+        }
+        words[d] = half[0] | half[1] << 16;
+      }
+      std::memcpy(rec + l * ams::kLaneChunkBytes, words, 16);
+      if (fmt == AMS_FMT_FP425_E2M2) rec[1024 + l] = (uint8_t)shared_byte;
+    }
+  }
+}
+
+void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* strip_in, int64_t K, uint8_t* const rows[16]) {
+  const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
+  for (int64_t j = 0; j < n_rec; j++) {
+    const uint8_t* rec = strip_in + j * fi.rec_bytes;
+    for (int l = 0; l < ams::kLanes; l++) {
+      uint8_t* row = rows[l & 15];
+      if (!row) continue;
+      const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
+      uint32_t words[4];
+      std::memcpy(words, rec + l * ams::kLaneChunkBytes, 16);
+      const uint32_t shared_byte = fmt == AMS_FMT_FP425_E2M2 ? rec[1024 + l] : 0;
+      for (int d = 0; d < 4; d++)
+        for (int h = 0; h < 2; h++) {
+          const uint32_t hw = (words[d] >> (16 * h)) & 0xFFFF;
+          if (fmt == AMS_FMT_FP425_E2M2) {
+            const uint32_t sh = (shared_byte >> (4 * h + d)) & 1;
+            const uint32_t sg[4] = {hw >> 15 & 1, hw >> 12 & 1, hw >> 14 & 1, hw >> 13 & 1};
+            for (int i = 0; i < 4; i++) {
+              const int64_t k = kbase + 8 * d + 4 * h + i;
+              if (k < K) row[k] = (uint8_t)(((sg[i] << 3 | ((hw >> (9 - 3 * i)) & 7)) << 1) | sh);
+            }
+          } else {
+            const uint32_t sh = hw >> 12 & 1;
+            for (int i = 0; i < 3; i++) {
+              const int64_t k = kbase + 6 * d + 3 * h + i;
+              if (k < K) row[k] = (uint8_t)((((hw >> (15 - i)) & 1) << 4 | ((hw >> (8 - 4 * i)) & 15)) << 1 | sh);
+            }
+          }
+        }
+    }
+  }
+}
+
+int check_shape(int fmt, int64_t N, int64_t K) {
+  if (!ams::format_info(fmt)) return AMS_ERR_FORMAT;
+  if (N <= 0 || K <= 0 || N > (int64_t)1 << 24 || K > (int64_t)1 << 24) return AMS_ERR_SHAPE;
+  return AMS_OK;
+}
+
+template <class F>
+void parallel_for(int64_t n, F&& body) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int64_t nt = std::max<int64_t>(1, std::min<int64_t>({(int64_t)(hw ? hw : 1), (int64_t)16, n}));
+  if (nt == 1) {
+    for (int64_t i = 0; i < n; i++) body(i);
+    return;
+  }
+  std::atomic<int64_t> next{0};
+  std::vector<std::thread> th;
+  for (int64_t t = 0; t < nt; t++)
+    th.emplace_back([&] {
+      for (int64_t i; (i = next.fetch_add(1)) < n;) body(i);
+    });
+  for (auto& t : th) t.join();
+}
+
+}  // namespace
+
+extern "C" {
+
+int ams_version(void) { return 100; }
+
+const char* ams_strerror(int code) {
+  switch (code) {
+    case AMS_OK: return "ok";
+    case AMS_ERR_FORMAT: return "unknown format";
+    case AMS_ERR_SHAPE: return "shape or argument out of range";
+    case AMS_ERR_NULL: return "null pointer";
+    case AMS_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case AMS_ERR_NONFINITE: return "weight is inf or NaN";
+    case AMS_ERR_LAUNCH: return "kernel launch failed";
+    case AMS_ERR_DEVICE: return "current device is not gfx950";
+    default: return "unknown error";
+  }
+}
+
+int ams_group_size(int fmt) {
+  const FormatInfo* fi = ams::format_info(fmt);
+  return fi ? fi->group : 0;
+}
+
+int ams_code_bits(int fmt) {
+  const FormatInfo* fi = ams::format_info(fmt);
+  return fi ? fi->code_bits : 0;
+}
+
+int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!bytes) return AMS_ERR_NULL;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  *bytes = (size_t)(ams::round_up(N, ams::kStripRows) / ams::kStripRows) * (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) *
+           (size_t)fi.rec_bytes;
+  return AMS_OK;
+}
+
+int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!bytes) return AMS_ERR_NULL;
+  if (fmt == AMS_FMT_FP533_E2M3)
+    *bytes = (size_t)2 * (size_t)((K + 2) / 3) * (size_t)N;  // one uint16 per 3 weights
+  else
+    *bytes = (size_t)34 * (size_t)((K + 63) / 64) * (size_t)N;  // 17 uint16 per 64 weights
+  return AMS_OK;
+}
+
+int ams_pack(int fmt, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed, uint16_t* scales,
+             uint8_t* codes_out) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!W || !packed || !scales) return AMS_ERR_NULL;
+  if (ldw < K) return AMS_ERR_SHAPE;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax};
+  const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
+  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
+  std::atomic<int> bad{0};
+  parallel_for(n_strips, [&](int64_t t) {
+    std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
+    const uint8_t* rows[16];
+    for (int r = 0; r < 16; r++) {
+      const int64_t n = t * 16 + r;
+      if (n >= N) {
+        rows[r] = nullptr;
+        continue;
+      }
+      uint8_t* c = buf.data() + (size_t)r * K;
+      if (!quantize_row(rq, W + n * ldw, K, c, scales + n)) bad.store(1);
+      rows[r] = c;
+      if (codes_out) std::memcpy(codes_out + n * K, c, (size_t)K);
+    }
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+  });
+  return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
+}
+
+int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* packed) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!codes || !packed) return AMS_ERR_NULL;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
+  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
+  std::atomic<int> bad{0};
+  parallel_for(n_strips, [&](int64_t t) {
+    const uint8_t* rows[16];
+    for (int r = 0; r < 16; r++) {
+      const int64_t n = t * 16 + r;
+      rows[r] = n < N ? codes + n * K : nullptr;
+      if (n >= N) continue;
+      for (int64_t k0 = 0; k0 < K; k0 += fi.group) {
+        const int64_t k1 = std::min<int64_t>(K, k0 + fi.group);
+        for (int64_t k = k0; k < k1; k++)
+          if ((rows[r][k] >> fi.code_bits) || ((rows[r][k] ^ rows[r][k0]) & 1)) bad.store(1);
+      }
+    }
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+  });
+  return bad.load() ? AMS_ERR_SHAPE : AMS_OK;
+}
+
+int ams_unpack_host(int fmt, const void* packed, int64_t N, int64_t K, uint8_t* codes) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!codes || !packed) return AMS_ERR_NULL;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
+  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
+  parallel_for(n_strips, [&](int64_t t) {
+    uint8_t* rows[16];
+    for (int r = 0; r < 16; r++) rows[r] = t * 16 + r < N ? codes + (t * 16 + r) * K : nullptr;
+    unpack_strip(fmt, fi, (const uint8_t*)packed + t * strip_bytes, K, rows);
+  });
+  return AMS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,170 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Restored weights must match bit for bit; Linear outputs must
+be within relative L2 1e-3 and max |error| <= 2e-2 of the output rms (unit-scale outputs)."""
+
+import numpy as np
+import pytest
+
+import paper_2510_16045_amd as ams
+from oracle import ams_oracle as O
+from paper_2510_16045_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]
+REL_L2_TOL = 1e-3
+MAX_ABS_TOL = 2e-2  # relative to rms(Y_ref)
+
+
+def dev(a: np.ndarray):
+    if a.dtype == np.float16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    return torch.from_numpy(a).cuda()
+
+
+def host16(t) -> np.ndarray:
+    return t.cpu().view(torch.int16).numpy().view(np.float16)
+
+
+def check_linear(y_gpu: np.ndarray, ref: np.ndarray, what=""):
+    y = y_gpu.astype(np.float64)
+    rel = np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-300)
+    rms = np.sqrt(np.mean(ref * ref))
+    mx = np.max(np.abs(y - ref)) / max(rms, 1e-300)
+    assert rel <= REL_L2_TOL, f"{what}: rel L2 {rel}"
+    assert mx <= MAX_ABS_TOL, f"{what}: max abs / rms {mx}"
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_dequant_every_code_through_the_kernel(fmt, ofmt):
+    # every remainder with both shared bits in every member position, over several records
+    g, nrem = ofmt.group, 1 << (ofmt.code_bits - 1)
+    rows = []
+    for sh in (0, 1):
+        for shift in range(g):
+            rem = (np.arange(nrem * g) // 1 + shift * 7) % nrem
+            rows.append(((rem << 1) | sh).astype(np.uint8))
+    codes = np.stack(rows)
+    codes = np.tile(codes, (3, 2))[:, : codes.shape[1] * 2 - 5]  # ragged tail, several strips' worth of rows
+    lsb = codes[:, ::g][:, : -(-codes.shape[1] // g)] & 1
+    codes = ((codes >> 1) << 1) | np.repeat(lsb, g, axis=1)[:, : codes.shape[1]]
+    N, K = codes.shape
+    s = (np.linspace(0.001, 9.0, N)).astype(np.float16)
+    wp = dev(ams.ams_pack_codes(fmt, codes))
+    got_u = host16(ams.ams_dequant(fmt, wp, None, N, K, scaled=False))
+    got_s = host16(ams.ams_dequant(fmt, wp, dev(s), N, K, scaled=True))
+    assert np.array_equal(got_u.view(np.uint16), O.dequant_unscaled(codes, ofmt).view(np.uint16))
+    assert np.array_equal(got_s.view(np.uint16), O.dequant_scaled(codes, s, ofmt).view(np.uint16))
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize(
+    "maker,N,K",
+    [(synth.gaussian_weights, 256, 768), (synth.gaussian_weights, 37, 1000), (synth.heavy_tail_weights, 80, 4100), (synth.gaussian_weights, 1, 3)],
+)
+def test_dequant_bit_exact(fmt, ofmt, maker, N, K):
+    W = maker(N, K, 31)
+    packed, scales = ams.ams_pack(fmt, W)
+    codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    got = host16(ams.ams_dequant(fmt, dev(packed), dev(scales), N, K, scaled=True))
+    assert np.array_equal(got.view(np.uint16), O.dequant_scaled(codes, o_scales, ofmt).view(np.uint16))
+    got = host16(ams.ams_dequant(fmt, dev(packed), None, N, K, scaled=False))
+    assert np.array_equal(got.view(np.uint16), O.dequant_unscaled(codes, ofmt).view(np.uint16))
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize(
+    "N,K,Ms",
+    [
+        (256, 768, (1, 2, 3, 4, 8, 16, 17, 32)),  # baseline config 1 (+ batch sweep)
+        (37, 1000, (1, 5, 32)),  # ragged strip, ragged record, ragged group
+        (48, 14336, (1, 16)),  # long K: many records per wave
+        (528, 4096, (1, 4, 32)),  # M=32 needs several activation phases
+        (16, 5, (1,)),
+    ],
+)
+def test_linear_matches_oracle(fmt, ofmt, N, K, Ms):
+    W = synth.gaussian_weights(N, K, 41)
+    packed, scales = ams.ams_pack(fmt, W)
+    codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    wp, sc = dev(packed), dev(scales)
+    for M in Ms:
+        X = synth.activations(M, K, 41 + M)
+        y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt))
+        check_linear(y, O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M}")
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_linear_heavy_tail_weights_and_outlier_activations(fmt, ofmt):
+    N, K = 64, 8192
+    W = synth.heavy_tail_weights(N, K, 51)
+    X = synth.activations(8, K, 51)
+    X[:, ::97] *= np.float16(30.0)  # channel-wise activation outliers
+    packed, scales = ams.ams_pack(fmt, W)
+    codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    y = host16(ams.ams_linear(dev(packed), dev(scales), dev(X), N, fmt))
+    check_linear(y, O.linear(codes, o_scales, X, ofmt), "heavy tail")
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_linear_one_hot_activation_returns_the_restored_weight(fmt, ofmt):
+    # a single product and a single rounding: Y[0, n] must be the scaled restored weight exactly
+    N, K = 40, 1000
+    W = synth.gaussian_weights(N, K, 61)
+    packed, scales = ams.ams_pack(fmt, W)
+    codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    want = O.dequant_scaled(codes, o_scales, ofmt)
+    wp, sc = dev(packed), dev(scales)
+    ks = list(range(0, 40)) + list(range(90, 135)) + [511, 512, 767, 768, 998, 999]
+    X = np.zeros((len(ks), K), dtype=np.float16)
+    for i, k in enumerate(ks):
+        X[i, k] = 1.0
+    for i0 in range(0, len(ks), 32):
+        y = host16(ams.ams_linear(wp, sc, dev(X[i0 : i0 + 32]), N, fmt))
+        for i in range(y.shape[0]):
+            # compared as numbers: a sum that starts from +0 cannot return the -0 of a negative zero code
+            assert np.array_equal(y[i], want[:, ks[i0 + i]]), ks[i0 + i]
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_linear_full_size_sampled_rows(fmt, ofmt):
+    # baseline config 2 shape (4096 x 4096, M=1) in the launch configuration the benchmark times;
+    # the oracle quantizes a sample of rows (rows are independent) and checks those outputs
+    W, X = synth.config2()
+    N, K = W.shape
+    packed, scales = ams.ams_pack(fmt, W)
+    y = host16(ams.ams_linear(dev(packed), dev(scales), dev(X), N, fmt)).astype(np.float64)
+    rows = np.r_[0:16, 2040:2056, 4080:4096, np.arange(5, N, 257)]
+    codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+    ref = O.linear(codes, o_scales, X, ofmt)
+    check_linear(y[:, rows].astype(np.float16), ref, "config 2 sample")
+    assert np.all(np.isfinite(y))
+
+
+@pytest.mark.parametrize("N,K,Ms", [(256, 768, (1, 2, 4, 8, 16, 32)), (37, 1000, (1, 7, 20)), (40, 14336, (1, 16))])
+def test_fp16_baseline_matches_oracle(N, K, Ms):
+    W = synth.gaussian_weights(N, K, 71)
+    w = dev(W)
+    for M in Ms:
+        X = synth.activations(M, K, 71 + M)
+        y = host16(ams.ams_fp16_linear(w, dev(X)))
+        check_linear(y, O.fp16_linear(W, X), f"fp16 N={N} K={K} M={M}")
+
+
+def test_device_entry_points_reject_bad_arguments():
+    lib = ams.load_library()
+    W = synth.gaussian_weights(16, 96, 1)
+    packed, scales = ams.ams_pack(ams.FP533, W)
+    wp, sc = dev(packed), dev(scales)
+    x = dev(synth.activations(1, 96, 1))
+    y = torch.empty((1, 16), dtype=torch.float16, device="cuda")
+    p = lambda t: t.data_ptr()
+    assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 0, 16, 96, 0, None) == -2
+    assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 33, 16, 96, 0, None) == -2
+    assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 1, 16, 96, 5, None) == -1
+    assert lib.ams_linear(None, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -3
+    assert lib.ams_linear(p(wp) + 2, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -4
+    assert lib.ams_dequant(3, p(wp), p(sc), p(y), 16, 96, 1, None) == -1
+    assert lib.ams_fp16_linear(p(x), p(x), p(y), 1, 1, 95, None) == -2
+    torch.cuda.synchronize()

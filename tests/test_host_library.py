@@ -1,0 +1,128 @@
+"""CPU-side tests of libams.so: it loads, exports every symbol include/ams.h declares,
+and its host quantizer / packer agrees bit for bit with the independent CPU oracle.
+No GPU call is made here."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_16045_amd as ams
+from oracle import ams_oracle as O
+from paper_2510_16045_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ams.load_library()
+    header = open(os.path.join(ROOT, "include", "ams.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = re.findall(r"\b(ams_[a-z0-9_]+)\s*\(", header)
+    assert len(set(names)) >= 11
+    for n in set(names):
+        assert hasattr(lib, n), n
+    assert lib.ams_version() >= 100
+    assert lib.ams_strerror(0) == b"ok"
+    assert [lib.ams_group_size(f) for f in (0, 1, 7)] == [3, 4, 0]
+    assert [lib.ams_code_bits(f) for f in (0, 1, 7)] == [6, 5, 0]
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("N,K", [(1, 1), (16, 96), (17, 100), (5, 13), (256, 768), (33, 1000)])
+def test_sizes(fmt, ofmt, N, K):
+    assert ams.ams_canonical_bytes(fmt, N, K) == O.canonical_packed_bytes(ofmt, N, K)
+    rec_k, rec_b = (96, 1024) if fmt == ams.FP533 else (128, 1088)
+    want = (-(-N // 16)) * (-(-K // rec_k)) * rec_b
+    assert ams.ams_packed_bytes(fmt, N, K) == want
+    # without padding the gfx950 layout takes exactly the bytes of the paper's packing
+    if N % 16 == 0 and K % rec_k == 0:
+        assert ams.ams_packed_bytes(fmt, N, K) == ams.ams_canonical_bytes(fmt, N, K)
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize(
+    "maker,N,K",
+    [
+        (synth.gaussian_weights, 256, 768),
+        (synth.gaussian_weights, 37, 1000),
+        (synth.gaussian_weights, 3, 5),
+        (synth.heavy_tail_weights, 64, 2050),
+    ],
+)
+def test_quantizer_matches_oracle_bit_for_bit(fmt, ofmt, maker, N, K):
+    W = maker(N, K, 21)
+    packed, scales, codes = ams.ams_pack(fmt, W, return_codes=True)
+    o_codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    assert np.array_equal(scales.view(np.uint16), o_scales.view(np.uint16))
+    assert np.array_equal(codes, o_codes.astype(np.uint8))
+    assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_quantizer_on_every_fp16_value(fmt, ofmt):
+    # every finite fp16 value as a weight, under several row scales (ties, saturation, subnormals)
+    bits = np.arange(1 << 16, dtype=np.uint16)
+    v = bits.view(np.float16)
+    v = v[np.isfinite(v)]
+    for top in (7.5, 7.0, 1.0, 0.0137, 60000.0):
+        row = v[np.abs(v.astype(np.float64)) <= top]
+        W = row[: (len(row) // 12) * 12].reshape(1, -1).copy()
+        W[0, 0] = np.float16(top)
+        _, scales, codes = ams.ams_pack(fmt, W, return_codes=True)
+        o_codes, o_scales, _ = O.ams_quantize(W, ofmt)
+        assert np.array_equal(scales, o_scales)
+        assert np.array_equal(codes, o_codes.astype(np.uint8))
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_degenerate_rows_and_errors(fmt, ofmt):
+    W = np.zeros((3, 24), dtype=np.float16)
+    W[1, 5] = np.float16(6e-8)
+    W[2, :] = np.float16(-3.0)
+    _, scales, codes = ams.ams_pack(fmt, W, return_codes=True)
+    o_codes, o_scales, _ = O.ams_quantize(W, ofmt)
+    assert np.array_equal(scales, o_scales) and np.array_equal(codes, o_codes)
+    W[0, 3] = np.float16(np.inf)
+    with pytest.raises(ams.AmsError, match="inf or NaN"):
+        ams.ams_pack(fmt, W)
+    with pytest.raises(ams.AmsError, match="unknown format"):
+        ams.ams_packed_bytes(9, 4, 4)
+    with pytest.raises(ams.AmsError, match="out of range"):
+        ams.ams_packed_bytes(fmt, 0, 4)
+    lib = ams.load_library()
+    assert lib.ams_pack(fmt, None, 4, 4, 4, None, None, None) == -3
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("N,K", [(16, 96), (16, 128), (19, 131), (1, 1), (48, 777)])
+def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
+    rng = np.random.default_rng(N * 1000 + K)
+    g = ofmt.group
+    rem = rng.integers(0, 1 << (ofmt.code_bits - 1), size=(N, K))
+    sh = rng.integers(0, 2, size=(N, -(-K // g)))
+    codes = ((rem << 1) | np.repeat(sh, g, axis=1)[:, :K]).astype(np.uint8)
+    packed = ams.ams_pack_codes(fmt, codes)
+    assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
+    # codes that went through the paper's own packing come back the same
+    via_paper = O.unpack_canonical(O.pack_canonical(codes, ofmt), ofmt, K).astype(np.uint8)
+    assert np.array_equal(ams.ams_unpack_host(fmt, ams.ams_pack_codes(fmt, via_paper), N, K), codes)
+    bad = codes.copy()
+    if K >= 2:
+        bad[0, 0] ^= 1  # group 0 no longer agrees in its last bit
+        with pytest.raises(ams.AmsError):
+            ams.ams_pack_codes(fmt, bad)
+
+
+def test_padding_is_zero_and_layout_is_deterministic():
+    W = synth.gaussian_weights(5, 50, 3)
+    for fmt in (ams.FP533, ams.FP425):
+        a, _ = ams.ams_pack(fmt, W)
+        b, _ = ams.ams_pack(fmt, W)
+        assert np.array_equal(a, b)
+        # rows 5..15 and k >= 50 are padding: a matrix of zero codes packs to all-zero bytes
+        z = ams.ams_pack_codes(fmt, np.zeros((5, 50), dtype=np.uint8))
+        assert not z.any()

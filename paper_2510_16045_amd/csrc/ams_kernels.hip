@@ -104,35 +104,41 @@ struct LinearArgs {
   const uint16_t* X;       // [M, K] fp16
   uint16_t* Y;             // [M, N] fp16
   int M, N, K;
-  int n_rec;          // records per strip
-  int recs_per_wave;  // L: records a wave takes per phase
-  int x_stride;       // halfs between activation rows in LDS
+  int n_rec;     // records per strip
+  int x_stride;  // halfs between activation rows inside a wave's LDS region
+  int x_region;  // halfs of one wave's LDS region
+  int x_phase;   // records of activations a wave stages at a time (a multiple of the ring depth)
+  int x_shift;   // log2 of the staging units per activation row, rounded up to a power of two
 };
 
+// Unconditional loads of one record (rec must be a valid record of the strip).
 template <int FMT>
-__device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, int strip, int rec, int lane, bool valid) {
+__device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, int strip, int rec, int lane) {
   if constexpr (FMT == FMT_FP16) {
+    // rows beyond N and K-chunks beyond K are redirected to the matrix's first 16 bytes
+    // and zeroed afterwards: keeps the loads free of control flow
     const int row = strip * 16 + (lane & 15);
     const int kq = lane >> 4;
 #pragma unroll
     for (int d = 0; d < 4; d++) {
       const int k = rec * 128 + 32 * d + 8 * kq;
-      const bool ok = valid && row < a.N && k < a.K;  // K is a multiple of 8
-      const u4* p = (const u4*)(a.W + ((size_t)row * a.K + k) * 2);
-      r.w[d] = ok ? __builtin_nontemporal_load(p) : u4{0, 0, 0, 0};
+      const bool ok = row < a.N && k < a.K;  // K is a multiple of 8
+      const size_t off = ok ? ((size_t)row * a.K + k) * 2 : 0;
+      const u4 v = __builtin_nontemporal_load((const u4*)(a.W + off));
+      const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
+      r.w[d] = u4{v[0] & keep, v[1] & keep, v[2] & keep, v[3] & keep};
     }
   } else {
     const uint8_t* base = a.W + ((size_t)strip * a.n_rec + rec) * Fmt<FMT>::REC_BYTES;
-    r.w = valid ? __builtin_nontemporal_load((const u4*)(base + lane * 16)) : u4{0, 0, 0, 0};
-    if constexpr (FMT == FMT_FP425) r.t = valid ? (uint32_t)__builtin_nontemporal_load(base + 1024 + lane) : 0u;
+    r.w = __builtin_nontemporal_load((const u4*)(base + lane * 16));
+    if constexpr (FMT == FMT_FP425) r.t = (uint32_t)__builtin_nontemporal_load(base + 1024 + lane);
   }
 }
 
-// Multiply one record (16 rows x REC_K) into the accumulators.  xrow points at this
-// lane's activation row in LDS at the first operand slot of this record's K-quarter.
+// Multiply one record (16 rows x REC_K) into the accumulators.  x0 / x1 point at this
+// lane's activation row(s) in LDS at the first operand slot of its K-quarter of the record.
 template <int FMT, int MT>
-__device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* xrow, bool has_x0, bool has_x1, int x_hi_off,
-                                        f4 acc[MT]) {
+__device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x0, const _Float16* x1, f4 acc[MT]) {
   h8 a[Fmt<FMT>::N_MFMA];
   if constexpr (FMT == FMT_FP425) {
     const uint32_t spread = spread_shared_fp425(r.t);
@@ -152,17 +158,12 @@ __device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x
 #pragma unroll
     for (int d = 0; d < 4; d++) a[d] = __builtin_bit_cast(h8, r.w[d]);
   }
-  const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int u = 0; u < Fmt<FMT>::N_MFMA; u++) {
     // FP16 records interleave the K-quarters per MFMA (32 consecutive k each)
     const int off = FMT == FMT_FP16 ? 32 * u : 8 * u;
-    h8 b0 = has_x0 ? *(const h8*)(xrow + off) : zero;
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u], b0, acc[0], 0, 0, 0);
-    if constexpr (MT == 2) {
-      h8 b1 = has_x1 ? *(const h8*)(xrow + x_hi_off + off) : zero;
-      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u], b1, acc[1], 0, 0, 0);
-    }
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u], *(const h8*)(x0 + off), acc[0], 0, 0, 0);
+    if constexpr (MT == 2) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u], *(const h8*)(x1 + off), acc[1], 0, 0, 0);
   }
 }
 
@@ -180,56 +181,173 @@ __device__ __forceinline__ int x_slot(int kk) {
   }
 }
 
-// Y[m, n] = fp16( s_n * sum_k value(code[n,k]) * X[m,k] ), one workgroup per strip of 16 rows.
-// blockDim.x = 64 * S wavefronts; phase p covers records [p*S*L, (p+1)*S*L), wave w the
-// L records starting at p*S*L + w*L.
-template <int FMT, int MT, int LMAX>
+// dword made of half `ia` (low) and half `ib` (high) of an array of packed half pairs
+__device__ __forceinline__ uint32_t pick2(const uint32_t* in, int ia, int ib) {
+  const uint32_t sel = (uint32_t)(2 * (ia & 1)) | (uint32_t)(2 * (ia & 1) + 1) << 8 | (uint32_t)(4 + 2 * (ib & 1)) << 16 |
+                       (uint32_t)(5 + 2 * (ib & 1)) << 24;
+  return __builtin_amdgcn_perm(in[ib >> 1], in[ia >> 1], sel);
+}
+
+// Activation staging.  A wave copies X[0..M) x [k0, k0+nk) into its LDS region in operand
+// order (zero beyond K), nk a multiple of the record size.  The copy is split in a load
+// half (global -> registers, no control flow around the loads) and a store half
+// (permute + LDS write) so that the loads can be issued ahead of the weight stream.
+// The work is cut in units of UNIT halfs; unit u covers row u >> x_shift, position
+// u & (2^x_shift - 1) (rows are padded to a power of two of units).
+template <int FMT>
+struct XUnit {
+  static constexpr int UNIT = FMT == FMT_FP533 ? 24 : 8;  // halfs permuted together
+  static constexpr int CH = UNIT / 8;                     // 16-byte chunks per unit
+  static constexpr int XU = FMT == FMT_FP533 ? 2 : 4;     // units a lane moves per pass
+};
+
+template <int FMT>
+struct XRegs {
+  u4 c[XUnit<FMT>::XU][XUnit<FMT>::CH];
+};
+
+template <int FMT>
+__device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int k0, int nk, int pass, int lane) {
+  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
+  const int upr = nk / UNIT;
+#pragma unroll
+  for (int i = 0; i < XU; i++) {
+    const int u = (pass * XU + i) * 64 + lane;
+    const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
+    const int k = k0 + UNIT * j;
+    const bool row_ok = m < a.M && j < upr;
+#pragma unroll
+    for (int e = 0; e < CH; e++) {
+      const bool ok = row_ok && k + 8 * e < a.K;
+      const size_t off = ok ? (size_t)m * a.K + k + 8 * e : 0;  // redirected loads are zeroed by x_store
+      xr.c[i][e] = *(const u4*)(a.X + off);
+    }
+  }
+}
+
+template <int FMT>
+__device__ __forceinline__ void x_store(const XRegs<FMT>& xr, _Float16* xs, const LinearArgs& a, int k0, int nk, int pass,
+                                        int lane) {
+  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
+  const int upr = nk / UNIT;
+#pragma unroll
+  for (int i = 0; i < XU; i++) {
+    const int u = (pass * XU + i) * 64 + lane;
+    const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
+    const int k = k0 + UNIT * j;
+    uint32_t in[4 * CH], out[4 * CH];
+#pragma unroll
+    for (int e = 0; e < CH; e++) {
+      const uint32_t keep = k + 8 * e < a.K ? 0xFFFFFFFFu : 0u;  // zero beyond K
+      in[4 * e] = xr.c[i][e][0] & keep, in[4 * e + 1] = xr.c[i][e][1] & keep;
+      in[4 * e + 2] = xr.c[i][e][2] & keep, in[4 * e + 3] = xr.c[i][e][3] & keep;
+    }
+    if constexpr (FMT == FMT_FP425) {
+#pragma unroll
+      for (int t = 0; t < 4; t++) out[t] = pick2(in, t, t + 4);
+    } else if constexpr (FMT == FMT_FP533) {
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+#pragma unroll
+        for (int t = 0; t < 3; t++) out[3 * q + t] = pick2(in, 6 * q + t, 6 * q + 3 + t);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; t++) out[t] = in[t];
+    }
+    if (m < a.M && j < upr) {
+      u4* dst = (u4*)(xs + m * a.x_stride + UNIT * j);
+#pragma unroll
+      for (int e = 0; e < CH; e++) dst[e] = u4{out[4 * e], out[4 * e + 1], out[4 * e + 2], out[4 * e + 3]};
+    }
+  }
+}
+
+// Element-by-element staging for activations whose rows are not 16-byte aligned (K % 8 != 0).
+template <int FMT>
+__device__ __forceinline__ void stage_x_unaligned(_Float16* xs, const LinearArgs& a, int k0, int nk, int lane) {
+  for (int idx = lane; idx < a.M * nk; idx += 64) {
+    const int m = idx / nk, kk = idx - m * nk;
+    const int k = k0 + kk;
+    const uint16_t v = k < a.K ? a.X[(size_t)m * a.K + k] : (uint16_t)0;
+    const int rl = kk / Fmt<FMT>::REC_K, kr = kk - rl * Fmt<FMT>::REC_K;
+    ((uint16_t*)xs)[m * a.x_stride + rl * Fmt<FMT>::REC_K + x_slot<FMT>(kr)] = v;
+  }
+}
+
+// Y[m, n] = fp16( s_n * sum_k value(code[n,k]) * X[m,k] ), one workgroup per strip of 16
+// output channels.  The S wavefronts of the workgroup take contiguous runs of the
+// strip's records.  Each wave keeps LR records in flight in a register ring whose
+// loads are unconditional (addresses clamped to the wave's last record) so that the
+// ring drains one record at a time; it stages the activations of its own K-range, XP
+// records at a time, in a private LDS region (no workgroup barrier inside the stream);
+// the partial 16x16 tiles are summed through LDS at the end.
+template <int FMT, int MT, int LR>
 __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* xs = (_Float16*)smem;
   constexpr int REC_K = Fmt<FMT>::REC_K;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = blockDim.x >> 6;
   const int strip = blockIdx.x;
-  const int L = a.recs_per_wave;
-  const int per_phase = S * L;
+  const int r_begin = (int)((int64_t)wave * a.n_rec / S), r_end = (int)((int64_t)(wave + 1) * a.n_rec / S);
+  const int r_last = r_end - 1;  // S <= n_rec, so every wave owns at least one record
+  _Float16* xs = (_Float16*)smem + (size_t)wave * a.x_region;
   const int m_lo = lane & 15, kq = lane >> 4;
-  const bool has_x0 = m_lo < a.M, has_x1 = m_lo + 16 < a.M;
+  // lanes whose activation row does not exist read row 0: they only feed output
+  // columns that are never stored
+  const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
+  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
+  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
 
   f4 acc[MT];
 #pragma unroll
   for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
 
-  for (int rec0 = 0; rec0 < a.n_rec; rec0 += per_phase) {
-    const int chunk_recs = min(per_phase, a.n_rec - rec0);
-    // 1. issue this wave's weight loads for the phase
-    LaneRec<FMT> recs[LMAX];
+  const int XP = a.x_phase;  // a multiple of LR
+  const bool vec_x = (a.K & 7) == 0;
+  constexpr int UNITS_PER_PASS = 64 * XUnit<FMT>::XU;
+  const int n_pass = ((a.M << a.x_shift) + UNITS_PER_PASS - 1) / UNITS_PER_PASS;
+
+  // the first activations are requested ahead of the weight stream
+  XRegs<FMT> xr;
+  if (vec_x) x_load<FMT>(xr, a, r_begin * REC_K, min(XP, r_end - r_begin) * REC_K, 0, lane);
+  __builtin_amdgcn_sched_barrier(0);
+
+  LaneRec<FMT> ring[LR];
 #pragma unroll
-    for (int q = 0; q < LMAX; q++) {
-      const int rl = wave * L + q;
-      load_rec<FMT>(recs[q], a, strip, rec0 + rl, lane, q < L && rl < chunk_recs);
+  for (int q = 0; q < LR; q++) {
+    load_rec<FMT>(ring[q], a, strip, min(r_begin + q, r_last), lane);
+    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
+  }
+
+  for (int xp0 = r_begin; xp0 < r_end; xp0 += XP) {
+    const int xp_cnt = min(XP, r_end - xp0);
+    if (vec_x) {
+      x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, 0, lane);
+      for (int pass = 1; pass < n_pass; pass++) {
+        x_load<FMT>(xr, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane);
+        x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane);
+      }
+    } else {
+      stage_x_unaligned<FMT>(xs, a, xp0 * REC_K, xp_cnt * REC_K, lane);
     }
-    // 2. stage the activations of the phase in operand order (zero beyond K)
-    if (rec0 > 0) __syncthreads();
-    const int chunk_k = chunk_recs * REC_K;
-    for (int idx = tid; idx < a.M * chunk_k; idx += blockDim.x) {
-      const int m = idx / chunk_k, kk = idx - m * chunk_k;
-      const int k = rec0 * REC_K + kk;
-      const uint16_t v = k < a.K ? a.X[(size_t)m * a.K + k] : (uint16_t)0;
-      const int rl = kk / REC_K, kr = kk - rl * REC_K;
-      ((uint16_t*)xs)[m * a.x_stride + rl * REC_K + x_slot<FMT>(kr)] = v;
-    }
-    __syncthreads();
-    // 3. restore + multiply
+    __builtin_amdgcn_wave_barrier();
+    int g = 0;
+    for (; g + LR <= xp_cnt; g += LR) {
 #pragma unroll
-    for (int q = 0; q < LMAX; q++) {
-      const int rl = wave * L + q;
-      if (q < L && rl < chunk_recs) {
-        const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
-        const _Float16* xrow = xs + m_lo * a.x_stride + rl * REC_K + lane_off;
-        mac_rec<FMT, MT>(recs[q], xrow, has_x0, has_x1, 16 * a.x_stride, acc);
+      for (int q = 0; q < LR; q++) {
+        mac_rec<FMT, MT>(ring[q], x0 + (g + q) * REC_K, x1 + (g + q) * REC_K, acc);
+        load_rec<FMT>(ring[q], a, strip, min(xp0 + g + q + LR, r_last), lane);
+        // keep the refill right behind its record: the ring then drains one record at a time
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // fewer than LR records left: this is the wave's last phase
+#pragma unroll
+    for (int q = 0; q < LR - 1; q++)
+      if (g + q < xp_cnt) mac_rec<FMT, MT>(ring[q], x0 + (g + q) * REC_K, x1 + (g + q) * REC_K, acc);
+    __builtin_amdgcn_wave_barrier();
+    if (vec_x && xp0 + XP < r_end) x_load<FMT>(xr, a, (xp0 + XP) * REC_K, min(XP, r_end - xp0 - XP) * REC_K, 0, lane);
   }
 
   // cross-wave reduction of the 16 x 16 tiles, then scale, convert, store
@@ -249,8 +367,7 @@ __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
         const int n = strip * 16 + 4 * kq + r;  // C[i][j]: lane = j + 16*(i/4), register i%4
         if (n < a.N) {
           float v = sum[r];
-          if constexpr (FMT != FMT_FP16)
-            v *= (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
+          if constexpr (FMT != FMT_FP16) v *= (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
           a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)v);
         }
       }
@@ -308,51 +425,80 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
 }
 
 // ---- host-side launch logic -------------------------------------------------
-constexpr int kXLdsBudget = 64 * 1024;  // bytes of LDS for staged activations per workgroup
+constexpr int kLdsBudget = 60 * 1024;  // bytes of LDS per workgroup
 
 struct Plan {
-  int S, L, lmax, x_stride;
+  int S, lr, x_phase, x_shift, x_stride, x_region;
   size_t lds;
 };
 
-// Choose wavefronts per workgroup (S) and records per wave per phase (L).
-Plan make_plan(int M, int64_t n_strips, int n_rec, int rec_k, int lmax_hi, int lmax_lo) {
+// Choose the wavefronts per workgroup (S), the ring depth (LR) and the activation
+// phase length.  The grid should be about one resident round of wavefronts (256 CUs x
+// 4 SIMDs x 4 waves at this kernel's register use): each wave then streams a long run of
+// records through its ring instead of many short-lived workgroups starting and
+// draining in lockstep.
+constexpr int kResidentWaves = 4096;
+
+Plan make_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
   Plan p;
-  int64_t want = (4096 + n_strips - 1) / n_strips;  // aim at >= 4096 wavefronts in the grid
-  int S = (int)std::min<int64_t>(16, std::max<int64_t>(1, want));
-  // keep at least ~4 records per wave when the grid is already large
-  while (S > 1 && (n_rec + S - 1) / S < 4 && n_strips * (S / 2) >= 4096) S /= 2;
+  const int mt = M > 16 ? 2 : 1;
+  const int64_t total_recs = n_strips * n_rec;
+  const int lr_max = fmt == FMT_FP16 ? 4 : 8;  // the baseline's records are four times larger
+  const int per_wave_target = (int)std::min<int64_t>(n_rec, std::max<int64_t>(2, (total_recs + kResidentWaves - 1) / kResidentWaves));
+  int S = std::min(16, std::max(1, (n_rec + per_wave_target - 1) / per_wave_target));
   S = std::min(S, n_rec);
-  int L;
   for (;;) {
     const int per_wave = (n_rec + S - 1) / S;
-    const int fit = kXLdsBudget / (M * S * rec_k * 2);
-    L = std::min(std::min(per_wave, lmax_hi), fit);
-    if (L >= 1 || S == 1) break;
-    S = std::max(1, S / 2);
+    int lr = lr_max;
+    while (lr > 2 && lr > per_wave) lr /= 2;
+    // activation rows a wave can hold: as many records as the LDS budget allows
+    int xp = kLdsBudget / (S * M * rec_k * 2);
+    xp = std::min(xp / lr * lr, (per_wave + lr - 1) / lr * lr);
+    if (xp < lr && lr > 2) {  // shrink the ring before shrinking the workgroup
+      lr = 2;
+      xp = kLdsBudget / (S * M * rec_k * 2);
+      xp = std::min(xp / lr * lr, (per_wave + lr - 1) / lr * lr);
+    }
+    if (xp >= lr || S == 1) {
+      p.S = S;
+      p.lr = lr;
+      p.x_phase = std::max(xp, lr);
+      break;
+    }
+    S = S / 2;
   }
-  if (L < 1) L = 1;
-  p.S = S;
-  p.L = L;
-  p.lmax = L <= lmax_lo ? lmax_lo : lmax_hi;
-  p.x_stride = S * L * rec_k + 8;  // +8 halfs: rows 16 bytes apart modulo the bank span
-  const size_t x_bytes = (size_t)M * p.x_stride * 2;
-  const size_t red_bytes = (size_t)S * (M > 16 ? 2 : 1) * 64 * 16;
-  p.lds = std::max(x_bytes, red_bytes);
+  {
+    const int units = p.x_phase * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    p.x_shift = 0;
+    while ((1 << p.x_shift) < units) p.x_shift++;
+  }
+  p.x_stride = p.x_phase * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+  p.x_region = M * p.x_stride;
+  p.lds = std::max((size_t)p.S * p.x_region * 2, (size_t)p.S * mt * 64 * 16);
   return p;
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-template <int FMT, int MT, int LMAX>
+template <int FMT, int MT, int LR>
 int launch_linear(const LinearArgs& a, const Plan& p, int64_t n_strips, hipStream_t st) {
-  auto kern = linear_kernel<FMT, MT, LMAX>;
+  auto kern = linear_kernel<FMT, MT, LR>;
   if (p.lds > 64 * 1024) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds) != hipSuccess)
       return AMS_ERR_LAUNCH;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)n_strips), dim3(64 * p.S), p.lds, st, a);
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
+}
+
+template <int FMT, int MT>
+int launch_linear_lr(const LinearArgs& a, const Plan& p, int64_t n_strips, hipStream_t st) {
+  switch (p.lr) {
+    case 8: if constexpr (FMT != FMT_FP16) return launch_linear<FMT, MT, 8>(a, p, n_strips, st); break;
+    case 4: return launch_linear<FMT, MT, 4>(a, p, n_strips, st);
+    case 2: return launch_linear<FMT, MT, 2>(a, p, n_strips, st);
+  }
+  return AMS_ERR_LAUNCH;
 }
 
 template <int FMT>
@@ -365,8 +511,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   constexpr int REC_K = Fmt<FMT>::REC_K;
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + REC_K - 1) / REC_K);
-  constexpr int HI = FMT == FMT_FP16 ? 4 : 16, LO = FMT == FMT_FP16 ? 1 : 4;
-  const Plan p = make_plan(M, n_strips, n_rec, REC_K, HI, LO);
+  const Plan p = make_plan(FMT, M, n_strips, n_rec, REC_K);
   LinearArgs a;
   a.W = (const uint8_t*)W;
   a.scales = scales;
@@ -376,12 +521,12 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.N = (int)N;
   a.K = (int)K;
   a.n_rec = n_rec;
-  a.recs_per_wave = p.L;
   a.x_stride = p.x_stride;
+  a.x_region = p.x_region;
+  a.x_phase = p.x_phase;
+  a.x_shift = p.x_shift;
   hipStream_t st = (hipStream_t)stream;
-  if (M <= 16)
-    return p.lmax == LO ? launch_linear<FMT, 1, LO>(a, p, n_strips, st) : launch_linear<FMT, 1, HI>(a, p, n_strips, st);
-  return p.lmax == LO ? launch_linear<FMT, 2, LO>(a, p, n_strips, st) : launch_linear<FMT, 2, HI>(a, p, n_strips, st);
+  return M <= 16 ? launch_linear_lr<FMT, 1>(a, p, n_strips, st) : launch_linear_lr<FMT, 2>(a, p, n_strips, st);
 }
 
 }  // namespace

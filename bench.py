@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true", help="also run the batch sweep M=1..32")
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
+                    help="only launch one Linear (e.g. gate_up:fp4.25:1, down:fp16:1) a few times, for rocprofv3, and exit")
     ap.add_argument("--copies-mb", type=int, default=1024, help="rotate through at least this many MB of weights per layer set")
     return ap.parse_args()
 
@@ -131,6 +133,30 @@ def cpu_baseline(seconds_hint=15.0):
     }
 
 
+def profile_kernel(args, shapes, torch, ams, synth):
+    """Launch one Linear `--steps` times on rotating copies (plain launches, no graph) for a profiler."""
+    name, fmt_s, m_s = args.profile_kernel.split(":")
+    N, K = shapes[name]
+    M = int(m_s)
+    W = synth.gaussian_weights(N, K, 100)
+    x = to_dev(synth.activations(M, K, 7), torch)
+    y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    n_copies = 6
+    if fmt_s == "fp16":
+        ws = [to_dev(W, torch) for _ in range(3)]
+        run = lambda i: ams.ams_fp16_linear(ws[i % 3], x, out=y)
+    else:
+        fmt = {"fp5.33": ams.FP533, "fp4.25": ams.FP425}[fmt_s]
+        p, s = ams.ams_pack(fmt, W)
+        ps = [to_dev(p, torch) for _ in range(n_copies)]
+        sc = to_dev(s, torch)
+        run = lambda i: ams.ams_linear(ps[i % n_copies], sc, x, N, fmt, out=y)
+    for i in range(args.steps):
+        run(i)
+    torch.cuda.synchronize()
+    print(json.dumps({"profiled": args.profile_kernel, "launches": args.steps}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -148,6 +174,9 @@ def main():
     torch.cuda.set_device(0)
 
     shapes = {"8b": synth.LLAMA8B_LAYERS, "70b": synth.LLAMA70B_LAYERS, "qwen": synth.QWEN_DOWN_LAYERS}[args.layers]
+    if args.profile_kernel:
+        profile_kernel(args, shapes, torch, ams, synth)
+        return
     maker = synth.heavy_tail_weights if args.layers == "70b" else synth.gaussian_weights
     t_setup = time.perf_counter()
     set_bytes = sum(n * k * 16 // 3 // 8 for n, k in shapes.values())

@@ -13,6 +13,8 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <mutex>
+#include <vector>
 
 #include "../../include/ams.h"
 #include "ams_layout.h"
@@ -91,7 +93,7 @@ struct LaneRec {
 template <>
 struct LaneRec<FMT_FP425> {
   u4 w;
-  uint32_t t;
+  uint8_t t;  // kept as a byte: it is widened where it is used, behind that record's own wait
 };
 template <>
 struct LaneRec<FMT_FP16> {
@@ -109,6 +111,10 @@ struct LinearArgs {
   int x_region;  // halfs of one wave's LDS region
   int x_phase;   // records of activations a wave stages at a time (a multiple of the ring depth)
   int x_shift;   // log2 of the staging units per activation row, rounded up to a power of two
+  int n_strips;  // strips of 16 output channels
+  int spw;       // stream kernel: strips per workgroup
+  int red_slots; // stream kernel: partial tiles a wave may park in LDS (strips its piece can touch)
+  int piece_q, piece_r;  // stream kernel: records per wave in a full workgroup: quotient, remainder
 };
 
 // Unconditional loads of one record (rec must be a valid record of the strip).
@@ -131,7 +137,7 @@ __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, i
   } else {
     const uint8_t* base = a.W + ((size_t)strip * a.n_rec + rec) * Fmt<FMT>::REC_BYTES;
     r.w = __builtin_nontemporal_load((const u4*)(base + lane * 16));
-    if constexpr (FMT == FMT_FP425) r.t = (uint32_t)__builtin_nontemporal_load(base + 1024 + lane);
+    if constexpr (FMT == FMT_FP425) r.t = __builtin_nontemporal_load(base + 1024 + lane);
   }
 }
 
@@ -141,7 +147,7 @@ template <int FMT, int MT>
 __device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x0, const _Float16* x1, f4 acc[MT]) {
   h8 a[Fmt<FMT>::N_MFMA];
   if constexpr (FMT == FMT_FP425) {
-    const uint32_t spread = spread_shared_fp425(r.t);
+    const uint32_t spread = spread_shared_fp425((uint32_t)r.t);
 #pragma unroll
     for (int d = 0; d < 4; d++) {
       uint32_t o[4];
@@ -198,7 +204,7 @@ template <int FMT>
 struct XUnit {
   static constexpr int UNIT = FMT == FMT_FP533 ? 24 : 8;  // halfs permuted together
   static constexpr int CH = UNIT / 8;                     // 16-byte chunks per unit
-  static constexpr int XU = FMT == FMT_FP533 ? 2 : 4;     // units a lane moves per pass
+  static constexpr int XU = 2;                            // units a lane moves per pass
 };
 
 template <int FMT>
@@ -207,12 +213,12 @@ struct XRegs {
 };
 
 template <int FMT>
-__device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int k0, int nk, int pass, int lane) {
+__device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int k0, int nk, int pass, int idx, int nthr) {
   constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
   const int upr = nk / UNIT;
 #pragma unroll
   for (int i = 0; i < XU; i++) {
-    const int u = (pass * XU + i) * 64 + lane;
+    const int u = (pass * XU + i) * nthr + idx;
     const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
     const int k = k0 + UNIT * j;
     const bool row_ok = m < a.M && j < upr;
@@ -227,12 +233,12 @@ __device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int 
 
 template <int FMT>
 __device__ __forceinline__ void x_store(const XRegs<FMT>& xr, _Float16* xs, const LinearArgs& a, int k0, int nk, int pass,
-                                        int lane) {
+                                        int idx, int nthr) {
   constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
   const int upr = nk / UNIT;
 #pragma unroll
   for (int i = 0; i < XU; i++) {
-    const int u = (pass * XU + i) * 64 + lane;
+    const int u = (pass * XU + i) * nthr + idx;
     const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
     const int k = k0 + UNIT * j;
     uint32_t in[4 * CH], out[4 * CH];
@@ -264,8 +270,8 @@ __device__ __forceinline__ void x_store(const XRegs<FMT>& xr, _Float16* xs, cons
 
 // Element-by-element staging for activations whose rows are not 16-byte aligned (K % 8 != 0).
 template <int FMT>
-__device__ __forceinline__ void stage_x_unaligned(_Float16* xs, const LinearArgs& a, int k0, int nk, int lane) {
-  for (int idx = lane; idx < a.M * nk; idx += 64) {
+__device__ __forceinline__ void stage_x_unaligned(_Float16* xs, const LinearArgs& a, int k0, int nk, int idx0, int nthr) {
+  for (int idx = idx0; idx < a.M * nk; idx += nthr) {
     const int m = idx / nk, kk = idx - m * nk;
     const int k = k0 + kk;
     const uint16_t v = k < a.K ? a.X[(size_t)m * a.K + k] : (uint16_t)0;
@@ -282,14 +288,14 @@ __device__ __forceinline__ void stage_x_unaligned(_Float16* xs, const LinearArgs
 // records at a time, in a private LDS region (no workgroup barrier inside the stream);
 // the partial 16x16 tiles are summed through LDS at the end.
 template <int FMT, int MT, int LR>
-__global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
+__global__ void __launch_bounds__(1024) phase_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = blockDim.x >> 6;
   const int strip = blockIdx.x;
-  const int r_begin = (int)((int64_t)wave * a.n_rec / S), r_end = (int)((int64_t)(wave + 1) * a.n_rec / S);
+  const int r_begin = (int)((unsigned)(wave * a.n_rec) / (unsigned)S), r_end = (int)((unsigned)((wave + 1) * a.n_rec) / (unsigned)S);
   const int r_last = r_end - 1;  // S <= n_rec, so every wave owns at least one record
   _Float16* xs = (_Float16*)smem + (size_t)wave * a.x_region;
   const int m_lo = lane & 15, kq = lane >> 4;
@@ -310,7 +316,7 @@ __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
 
   // the first activations are requested ahead of the weight stream
   XRegs<FMT> xr;
-  if (vec_x) x_load<FMT>(xr, a, r_begin * REC_K, min(XP, r_end - r_begin) * REC_K, 0, lane);
+  if (vec_x) x_load<FMT>(xr, a, r_begin * REC_K, min(XP, r_end - r_begin) * REC_K, 0, lane, 64);
   __builtin_amdgcn_sched_barrier(0);
 
   LaneRec<FMT> ring[LR];
@@ -323,13 +329,13 @@ __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
   for (int xp0 = r_begin; xp0 < r_end; xp0 += XP) {
     const int xp_cnt = min(XP, r_end - xp0);
     if (vec_x) {
-      x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, 0, lane);
+      x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, 0, lane, 64);
       for (int pass = 1; pass < n_pass; pass++) {
-        x_load<FMT>(xr, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane);
-        x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane);
+        x_load<FMT>(xr, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane, 64);
+        x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane, 64);
       }
     } else {
-      stage_x_unaligned<FMT>(xs, a, xp0 * REC_K, xp_cnt * REC_K, lane);
+      stage_x_unaligned<FMT>(xs, a, xp0 * REC_K, xp_cnt * REC_K, lane, 64);
     }
     __builtin_amdgcn_wave_barrier();
     int g = 0;
@@ -347,7 +353,7 @@ __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
     for (int q = 0; q < LR - 1; q++)
       if (g + q < xp_cnt) mac_rec<FMT, MT>(ring[q], x0 + (g + q) * REC_K, x1 + (g + q) * REC_K, acc);
     __builtin_amdgcn_wave_barrier();
-    if (vec_x && xp0 + XP < r_end) x_load<FMT>(xr, a, (xp0 + XP) * REC_K, min(XP, r_end - xp0 - XP) * REC_K, 0, lane);
+    if (vec_x && xp0 + XP < r_end) x_load<FMT>(xr, a, (xp0 + XP) * REC_K, min(XP, r_end - xp0 - XP) * REC_K, 0, lane, 64);
   }
 
   // cross-wave reduction of the 16 x 16 tiles, then scale, convert, store
@@ -371,6 +377,250 @@ __global__ void __launch_bounds__(1024) linear_kernel(LinearArgs a) {
           a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)v);
         }
       }
+    }
+  }
+}
+
+// Scale a finished 16x16 tile (C[i][j]: lane = j + 16*(i/4), register i%4), convert, store.
+template <int FMT, int MT>
+__device__ __forceinline__ void store_tile(const f4 t[MT], const LinearArgs& a, int strip, int lane) {
+  const int m_lo = lane & 15, kq = lane >> 4;
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) {
+    const int m = m_lo + 16 * mt;
+    if (m < a.M) {
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int n = strip * 16 + 4 * kq + r;
+        if (n < a.N) {
+          float v = t[mt][r];
+          if constexpr (FMT != FMT_FP16) v *= (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
+          a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)v);
+        }
+      }
+    }
+  }
+}
+
+// fp32 multipliers s_n * 2^14 of the four output channels a lane holds of a strip's tile
+template <int FMT>
+__device__ __forceinline__ f4 load_scales(const LinearArgs& a, int strip, int lane) {
+  f4 sc = {1.0f, 1.0f, 1.0f, 1.0f};
+  if constexpr (FMT != FMT_FP16) {
+    const int n0 = strip * 16 + 4 * (lane >> 4);
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      const int n = min(n0 + r, a.N - 1);  // clamped: rows beyond N are never stored
+      sc[r] = (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
+    }
+  }
+  return sc;
+}
+
+// Multiply a finished 16x16 tile (C[i][j]: lane = j + 16*(i/4), register i%4) by the scales, convert, store.
+template <int MT>
+__device__ __forceinline__ void store_tile_scaled(const f4 t[MT], const f4 sc, const LinearArgs& a, int strip, int lane) {
+  const int m_lo = lane & 15, kq = lane >> 4;
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) {
+    const int m = m_lo + 16 * mt;
+    if (m < a.M) {
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int n = strip * 16 + 4 * kq + r;
+        if (n < a.N) a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)(t[mt][r] * sc[r]));
+      }
+    }
+  }
+}
+
+// All threads of a workgroup copy X[0..M) x [0, k_pad) into LDS in operand order (zero beyond K).
+template <int FMT>
+__device__ __forceinline__ void stage_x_block(_Float16* xs, const LinearArgs& a, int k_pad, int tid, int nthr) {
+  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH;
+  if ((a.K & 7) != 0) {  // rows not 16-byte aligned
+    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
+    return;
+  }
+  const int upr = k_pad / UNIT;
+  const int total = a.M << a.x_shift;
+  for (int u = tid; u < total; u += nthr) {
+    const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
+    if (j >= upr) continue;
+    const int k = UNIT * j;
+    const uint16_t* src = a.X + (size_t)m * a.K + k;
+    uint32_t in[4 * CH], out[4 * CH];
+#pragma unroll
+    for (int e = 0; e < CH; e++) {
+      const u4 c = k + 8 * e < a.K ? *(const u4*)(src + 8 * e) : u4{0, 0, 0, 0};
+      in[4 * e] = c[0], in[4 * e + 1] = c[1], in[4 * e + 2] = c[2], in[4 * e + 3] = c[3];
+    }
+    if constexpr (FMT == FMT_FP425) {
+#pragma unroll
+      for (int t = 0; t < 4; t++) out[t] = pick2(in, t, t + 4);
+    } else if constexpr (FMT == FMT_FP533) {
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+#pragma unroll
+        for (int t = 0; t < 3; t++) out[3 * q + t] = pick2(in, 6 * q + t, 6 * q + 3 + t);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; t++) out[t] = in[t];
+    }
+    u4* dst = (u4*)(xs + m * a.x_stride + UNIT * j);
+#pragma unroll
+    for (int e = 0; e < CH; e++) dst[e] = u4{out[4 * e], out[4 * e + 1], out[4 * e + 2], out[4 * e + 3]};
+  }
+}
+
+// The streaming Linear.  A workgroup owns `spw` consecutive strips, i.e. a contiguous
+// run of spw * n_rec records (records of consecutive strips are adjacent in memory),
+// and its S wavefronts cut that run into S contiguous pieces, whatever the strip
+// boundaries: every wave streams the same number of bytes through its register ring.
+// The whole activation matrix is staged once per workgroup in LDS (operand order).
+// A strip that lies inside one wave's piece is finished by that wave from registers;
+// a strip cut by piece boundaries is summed, in wave order, through LDS after the one
+// barrier that ends the stream.  The grid is one resident round of workgroups.
+template <int FMT, int MT, int LR>
+__global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int REC_K = Fmt<FMT>::REC_K;
+  const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int S = nthr >> 6;
+  const int strip0 = blockIdx.x * a.spw;
+  const int ns = min(a.spw, a.n_strips - strip0);
+  const int F = ns * a.n_rec;  // records of this workgroup
+  // balanced pieces: wave w takes piece_q records, the first piece_r waves one more
+  // (the host supplies the quotient for full workgroups: no 64-bit division in here)
+  int piece_q = a.piece_q, piece_r = a.piece_r;
+  if (ns != a.spw) {
+    piece_q = (int)((unsigned)F / (unsigned)S);
+    piece_r = F - piece_q * S;
+  }
+  const int f0 = wave * piece_q + min(wave, piece_r), f1 = f0 + piece_q + (wave < piece_r ? 1 : 0);
+  const int f_last = max(f1 - 1, 0);
+  _Float16* xs = (_Float16*)smem;
+  f4* red = (f4*)(smem + (size_t)a.x_region * 2);         // [S][red_slots][MT][64]
+  const int m_lo = lane & 15, kq = lane >> 4;
+  const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
+  // lanes whose activation row does not exist read row 0: they only feed output columns never stored
+  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
+  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
+
+  // Activations: once per workgroup, in operand order.  Units beyond the first pass (large
+  // M x K) and unaligned rows are staged by loops that run to completion first; the first
+  // pass is only requested here and stored after the head of the weight stream has been
+  // requested too, so that both are in flight together and the stream starts as soon as
+  // its first record lands.  Waves whose units all fall outside the matrix skip the pass.
+  const int k_pad = a.n_rec * REC_K;
+  const bool vec_x = (a.K & 7) == 0;
+  const int total_units = a.M << a.x_shift;
+  const int units_per_pass = nthr * XUnit<FMT>::XU;
+  XRegs<FMT> xr;
+  if (vec_x) {
+    for (int pass = 1; pass * units_per_pass < total_units; pass++) {
+      x_load<FMT>(xr, a, 0, k_pad, pass, tid, nthr);
+      x_store<FMT>(xr, xs, a, 0, k_pad, pass, tid, nthr);
+    }
+  } else {
+    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
+  }
+  const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
+  if (wave_has_x) x_load<FMT>(xr, a, 0, k_pad, 0, tid, nthr);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // the head of the weight stream: LR records in flight per wave
+  int pf = min(f0, f_last);  // prefetch cursor (flat index, strip, record), clamped to the wave's last record
+  int ps = (int)((unsigned)pf / (unsigned)a.n_rec), pr = pf - ps * a.n_rec;
+  const int s_first0 = ps, rk0 = pr;
+  // scales of the first strip this wave will finish (the first one that starts inside its piece)
+  const f4 scale0 = load_scales<FMT>(a, min(strip0 + (pr == 0 ? ps : ps + 1), a.n_strips - 1), lane);
+  LaneRec<FMT> ring[LR];
+#pragma unroll
+  for (int q = 0; q < LR; q++) {
+    load_rec<FMT>(ring[q], a, strip0 + ps, pr, lane);
+    if (pf < f_last) {
+      pf++;
+      if (++pr == a.n_rec) pr = 0, ps++;
+    }
+    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
+  }
+
+  if (wave_has_x) x_store<FMT>(xr, xs, a, 0, k_pad, 0, tid, nthr);
+  __syncthreads();
+
+  f4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
+  // a wave with records starts its prefetch cursor at f0, so (ps, pr) at that moment
+  // were its first strip and the record inside it
+  const int s_first = s_first0;
+  int rk = rk0;  // record inside the current strip
+  int f = f0;
+  f4* my_red = red + (size_t)wave * a.red_slots * MT * 64 + lane;  // this wave's tiles: [slot][MT][64]
+
+  // One record: multiply, refill the ring slot; when the strip (or the wave's piece)
+  // ends here, park the partial tile in LDS.  Nothing in here touches global memory
+  // except the refill, so the ring keeps draining one record at a time.
+  auto step = [&](LaneRec<FMT>& slot) {
+    mac_rec<FMT, MT>(slot, x0 + rk * REC_K, x1 + rk * REC_K, acc);
+    load_rec<FMT>(slot, a, strip0 + ps, pr, lane);
+    if (pf < f_last) {
+      pf++;
+      if (++pr == a.n_rec) pr = 0, ps++;
+    }
+    f++;
+    rk++;
+    if (rk == a.n_rec || f == f1) {
+#pragma unroll
+      for (int i = 0; i < MT; i++) {
+        my_red[i * 64] = acc[i];
+        acc[i] = f4{0, 0, 0, 0};
+      }
+      my_red += MT * 64;
+      rk = 0;
+    }
+  };
+
+  while (f + LR <= f1) {
+#pragma unroll
+    for (int q = 0; q < LR; q++) {
+      step(ring[q]);
+      // keep the refill right behind its record
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < LR - 1; q++)
+    if (f < f1) step(ring[q]);
+
+  // Finish the strips.  The wave that holds a strip's first record owns it: it adds the
+  // head tiles (slot 0) of the waves after it whose pieces still lie in that strip, in
+  // wave order, and stores.  The tile reads do not depend on each other, so they overlap.
+  __syncthreads();
+  if (f1 > f0) {
+    const int s_begin = rk0 == 0 ? s_first : s_first + 1;  // first strip that starts inside this piece
+    for (int s = s_begin; s * a.n_rec < f1; s++) {
+      const int se = (s + 1) * a.n_rec;
+      f4 sum[MT];
+#pragma unroll
+      for (int i = 0; i < MT; i++) sum[i] = red[(((size_t)wave * a.red_slots + (s - s_first)) * MT + i) * 64 + lane];
+      if (se > f1) {  // the strip runs on into the next waves' pieces
+#pragma unroll
+        for (int d = 1; d < 16; d++) {
+          const int w2 = min(wave + d, S - 1);
+          const int g0 = w2 * piece_q + min(w2, piece_r), g1 = g0 + piece_q + (w2 < piece_r ? 1 : 0);
+          const bool take = wave + d < S && g0 < se && g1 > g0;
+#pragma unroll
+          for (int i = 0; i < MT; i++) {
+            // selected, not multiplied: a tile that is not taken may be uninitialised LDS
+            const f4 t = red[(((size_t)w2 * a.red_slots + 0) * MT + i) * 64 + lane];
+            sum[i] += take ? t : f4{0, 0, 0, 0};
+          }
+        }
+      }
+      store_tile_scaled<MT>(sum, s == s_begin ? scale0 : load_scales<FMT>(a, strip0 + s, lane), a, strip0 + s, lane);
     }
   }
 }
@@ -425,7 +675,8 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
 }
 
 // ---- host-side launch logic -------------------------------------------------
-constexpr int kLdsBudget = 60 * 1024;  // bytes of LDS per workgroup
+constexpr int kLdsBudget = 60 * 1024;   // phase kernel: bytes of LDS for staged activations per workgroup
+constexpr int kLdsMaxBytes = 160 * 1024;  // LDS of a gfx950 compute unit
 
 struct Plan {
   int S, lr, x_phase, x_shift, x_stride, x_region;
@@ -480,23 +731,83 @@ Plan make_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-template <int FMT, int MT, int LR>
-int launch_linear(const LinearArgs& a, const Plan& p, int64_t n_strips, hipStream_t st) {
-  auto kern = linear_kernel<FMT, MT, LR>;
-  if (p.lds > 64 * 1024) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds) != hipSuccess)
-      return AMS_ERR_LAUNCH;
-  }
-  hipLaunchKernelGGL(kern, dim3((unsigned)n_strips), dim3(64 * p.S), p.lds, st, a);
+constexpr int kNumCU = 256;             // MI355X compute units
+constexpr int kStreamLdsMax = 150 * 1024;  // of the 160 KiB a workgroup may use
+
+struct StreamPlan {
+  bool ok;
+  int S, lr, spw, grid, x_shift, x_stride, x_region, red_slots;
+  size_t lds;
+};
+
+// Launch shape of the streaming kernel: one workgroup of 16 wavefronts per CU, each
+// owning an equal run of whole strips.  Not applicable (ok = false) when the staged
+// activations M x K do not fit in LDS.
+StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
+  StreamPlan p;
+  const int mt = M > 16 ? 2 : 1;
+  // strips per workgroup: one resident round, but at most 32 (a wave parks one tile per strip it touches)
+  p.spw = (int)std::min<int64_t>(32, (n_strips + kNumCU - 1) / kNumCU);
+  p.grid = (int)((n_strips + p.spw - 1) / p.spw);
+  const int64_t F = (int64_t)p.spw * n_rec;
+  p.S = (int)std::min<int64_t>(16, std::max<int64_t>(1, F));
+  const int per_wave = (int)(F / p.S);
+  const int lr_max = fmt == FMT_FP16 ? 2 : 8;  // the baseline's records are four times larger
+  p.lr = lr_max;
+  while (p.lr > 2 && p.lr > per_wave) p.lr /= 2;
+  const int k_pad = n_rec * rec_k;
+  const int units = k_pad / (fmt == FMT_FP533 ? 24 : 8);
+  p.x_shift = 0;
+  while ((1 << p.x_shift) < units) p.x_shift++;
+  p.x_stride = k_pad + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+  p.x_region = M * p.x_stride;
+  const int per_wave_max = (int)((F + p.S - 1) / p.S);
+  p.red_slots = (per_wave_max - 1) / n_rec + 2;
+  p.lds = (size_t)p.x_region * 2 + (size_t)p.S * p.red_slots * mt * 64 * 16 + (size_t)p.S * 4;
+  p.ok = p.lds <= (size_t)kStreamLdsMax;
+  return p;
+}
+
+// Kernels that use more than 64 KiB of dynamic LDS must have their limit raised first;
+// that is a per-function, per-device property, remembered here so it is done once.
+bool raise_lds_limit(const void* kern) {
+  struct Entry {
+    const void* kern;
+    int dev;
+  };
+  static std::mutex mu;
+  static std::vector<Entry> done;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : done)
+    if (e.kern == kern && e.dev == dev) return true;
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMaxBytes) != hipSuccess) return false;
+  done.push_back({kern, dev});
+  return true;
+}
+
+template <class Kern>
+int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  if (lds > 64 * 1024 && !raise_lds_limit((const void*)kern)) return AMS_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * S), lds, st, a);
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
 template <int FMT, int MT>
-int launch_linear_lr(const LinearArgs& a, const Plan& p, int64_t n_strips, hipStream_t st) {
-  switch (p.lr) {
-    case 8: if constexpr (FMT != FMT_FP16) return launch_linear<FMT, MT, 8>(a, p, n_strips, st); break;
-    case 4: return launch_linear<FMT, MT, 4>(a, p, n_strips, st);
-    case 2: return launch_linear<FMT, MT, 2>(a, p, n_strips, st);
+int launch_by_ring(bool stream, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  if (stream) {
+    switch (lr) {
+      case 8: if constexpr (FMT != FMT_FP16) return launch(stream_kernel<FMT, MT, 8>, a, grid, S, lds, st); break;
+      case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
+      case 2: return launch(stream_kernel<FMT, MT, 2>, a, grid, S, lds, st);
+    }
+  } else {
+    switch (lr) {
+      case 8: if constexpr (FMT != FMT_FP16) return launch(phase_kernel<FMT, MT, 8>, a, grid, S, lds, st); break;
+      case 4: return launch(phase_kernel<FMT, MT, 4>, a, grid, S, lds, st);
+      case 2: return launch(phase_kernel<FMT, MT, 2>, a, grid, S, lds, st);
+    }
   }
   return AMS_ERR_LAUNCH;
 }
@@ -511,7 +822,6 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   constexpr int REC_K = Fmt<FMT>::REC_K;
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + REC_K - 1) / REC_K);
-  const Plan p = make_plan(FMT, M, n_strips, n_rec, REC_K);
   LinearArgs a;
   a.W = (const uint8_t*)W;
   a.scales = scales;
@@ -521,12 +831,31 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.N = (int)N;
   a.K = (int)K;
   a.n_rec = n_rec;
+  a.n_strips = (int)n_strips;
+  hipStream_t st = (hipStream_t)stream;
+  const StreamPlan sp = make_stream_plan(FMT, M, n_strips, n_rec, REC_K);
+  if (sp.ok) {
+    a.x_stride = sp.x_stride;
+    a.x_region = sp.x_region;
+    a.x_phase = 0;
+    a.x_shift = sp.x_shift;
+    a.spw = sp.spw;
+    a.red_slots = sp.red_slots;
+    a.piece_q = (int)(((int64_t)sp.spw * n_rec) / sp.S);
+    a.piece_r = (int)(((int64_t)sp.spw * n_rec) % sp.S);
+    return M <= 16 ? launch_by_ring<FMT, 1>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st)
+                   : launch_by_ring<FMT, 2>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st);
+  }
+  const Plan p = make_plan(FMT, M, n_strips, n_rec, REC_K);
   a.x_stride = p.x_stride;
   a.x_region = p.x_region;
   a.x_phase = p.x_phase;
   a.x_shift = p.x_shift;
-  hipStream_t st = (hipStream_t)stream;
-  return M <= 16 ? launch_linear_lr<FMT, 1>(a, p, n_strips, st) : launch_linear_lr<FMT, 2>(a, p, n_strips, st);
+  a.spw = 1;
+  a.red_slots = 0;
+  a.piece_q = a.piece_r = 0;
+  return M <= 16 ? launch_by_ring<FMT, 1>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st)
+                 : launch_by_ring<FMT, 2>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st);
 }
 
 }  // namespace

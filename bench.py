@@ -30,6 +30,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
+# by what the same counter reads for a 256 MiB device copy (profiles/stream_kernel_gate_up_fp533_hbm_traffic.md)
+MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77604 + 56) * 1024}
 FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2"}
 
 
@@ -43,6 +46,7 @@ def parse_args():
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
+                   
                     help="only launch one Linear (e.g. gate_up:fp4.25:1, down:fp16:1) a few times, for rocprofv3, and exit")
     ap.add_argument("--copies-mb", type=int, default=1024, help="rotate through at least this many MB of weights per layer set")
     return ap.parse_args()
@@ -136,6 +140,15 @@ def cpu_baseline(seconds_hint=15.0):
 def profile_kernel(args, shapes, torch, ams, synth):
     """Launch one Linear `--steps` times on rotating copies (plain launches, no graph) for a profiler."""
     name, fmt_s, m_s = args.profile_kernel.split(":")
+    if name == "copy":  # calibration for HBM traffic counters: a device copy of a known size (fmt field = MiB)
+        n = int(fmt_s) << 20
+        src = [torch.full((n,), 7, dtype=torch.uint8, device="cuda") for _ in range(3)]
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        for i in range(args.steps):
+            dst.copy_(src[i % 3])
+        torch.cuda.synchronize()
+        print(json.dumps({"profiled": args.profile_kernel, "launches": args.steps, "bytes_read": n, "bytes_written": n}))
+        return
     N, K = shapes[name]
     M = int(m_s)
     W = synth.gaussian_weights(N, K, 100)
@@ -251,9 +264,10 @@ def main():
     t_dom = time_launches(torch, lambda i: ams.ams_linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, out=ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
     roofline = {
-        "bound": "hbm", "kernel": f"linear_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
+        "bound": "hbm", "kernel": f"stream_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes, "traffic": None,
+        "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes,
+        "traffic": MEASURED_TRAFFIC_BYTES.get((dl.name, dom["fmt"], M)) if args.layers == "8b" else None,
     }
 
     sweep = None

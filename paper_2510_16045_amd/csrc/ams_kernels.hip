@@ -115,7 +115,8 @@ struct LinearArgs {
   int n_strips;  // strips of 16 output channels
   int spw;       // stream kernel: strips per workgroup
   int red_slots; // stream kernel: partial tiles a wave may park in LDS (strips its piece can touch)
-  int piece_q, piece_r;  // stream kernel: records per wave in a full workgroup: quotient, remainder
+  int piece_q, piece_r;  // stream kernel: pairs per wave in a full workgroup: quotient, remainder
+  int rc;                // stream kernel: records per strip in one phase of K
 };
 
 // Unconditional loads of one record (rec must be a valid record of the strip).
@@ -474,14 +475,18 @@ __device__ __forceinline__ void stage_x_block(_Float16* xs, const LinearArgs& a,
   }
 }
 
-// The streaming Linear.  A workgroup owns `spw` consecutive strips, i.e. a contiguous
-// run of spw * n_rec records (records of consecutive strips are adjacent in memory),
-// and its S wavefronts cut that run into S contiguous pieces, whatever the strip
-// boundaries: every wave streams the same number of bytes through its register ring.
-// The whole activation matrix is staged once per workgroup in LDS (operand order).
-// A strip that lies inside one wave's piece is finished by that wave from registers;
-// a strip cut by piece boundaries is summed, in wave order, through LDS after the one
-// barrier that ends the stream.  The grid is one resident round of workgroups.
+// The streaming Linear.  A workgroup owns `spw` consecutive strips and walks K in
+// phases of `rc` records per strip (one phase when the activations M x K fit in LDS).
+// Inside a phase its work is the list of (strip, record) pairs in strip-major order;
+// the S wavefronts cut that list into S equal contiguous pieces, whatever the strip
+// boundaries, so every wave streams the same number of bytes through its register ring
+// (records of a strip are adjacent in memory, and with one phase those of consecutive
+// strips are too).  The pieces are the same in every phase, so a wave meets the same
+// strips again: its partial 16x16 tiles live in LDS slots and are swapped in and out
+// of the accumulator registers where its piece crosses a strip boundary.  The
+// activations of a phase are staged once per workgroup in LDS (operand order).  After
+// the last phase the wave holding a strip's first record adds the tiles of the waves
+// after it, in wave order, scales and stores.  The grid is one resident round.
 template <int FMT, int MT, int LR>
 __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -491,128 +496,137 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   const int S = nthr >> 6;
   const int strip0 = blockIdx.x * a.spw;
   const int ns = min(a.spw, a.n_strips - strip0);
-  const int F = ns * a.n_rec;  // records of this workgroup
-  // balanced pieces: wave w takes piece_q records, the first piece_r waves one more
+  const int RC = a.rc;
+  const int P = ns * RC;  // (strip, record) pairs of one phase
+  // balanced pieces: wave w takes piece_q pairs, the first piece_r waves one more
   // (the host supplies the quotient for full workgroups: no 64-bit division in here)
   int piece_q = a.piece_q, piece_r = a.piece_r;
   if (ns != a.spw) {
-    piece_q = (int)((unsigned)F / (unsigned)S);
-    piece_r = F - piece_q * S;
+    piece_q = (int)((unsigned)P / (unsigned)S);
+    piece_r = P - piece_q * S;
   }
-  const int f0 = wave * piece_q + min(wave, piece_r), f1 = f0 + piece_q + (wave < piece_r ? 1 : 0);
-  const int f_last = max(f1 - 1, 0);
+  const int g0 = wave * piece_q + min(wave, piece_r), g1 = g0 + piece_q + (wave < piece_r ? 1 : 0);
+  const int g_last = max(g1 - 1, 0);
+  const int s_first = (int)((unsigned)min(g0, g_last) / (unsigned)RC);  // strip of the piece's first pair
+  const int j_first = min(g0, g_last) - s_first * RC;                   // its record inside the phase
   _Float16* xs = (_Float16*)smem;
-  f4* red = (f4*)(smem + (size_t)a.x_region * 2);         // [S][red_slots][MT][64]
+  f4* red = (f4*)(smem + (size_t)a.x_region * 2);  // [S][red_slots][MT][64]
+  f4* const my_red = red + (size_t)wave * a.red_slots * MT * 64 + lane;  // this wave's tiles: [slot][MT][64]
   const int m_lo = lane & 15, kq = lane >> 4;
   const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
   // lanes whose activation row does not exist read row 0: they only feed output columns never stored
   const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
   const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
 
-  // Activations: once per workgroup, in operand order.  Units beyond the first pass (large
-  // M x K) and unaligned rows are staged by loops that run to completion first; the first
-  // pass is only requested here and stored after the head of the weight stream has been
-  // requested too, so that both are in flight together and the stream starts as soon as
-  // its first record lands.  Waves whose units all fall outside the matrix skip the pass.
-  const int k_pad = a.n_rec * REC_K;
+  // scales of the first strip this wave will finish (the first one that starts inside its piece)
+  const f4 scale0 = load_scales<FMT>(a, min(strip0 + (j_first == 0 ? s_first : s_first + 1), a.n_strips - 1), lane);
+  for (int t = 0; t < a.red_slots * MT; t++) my_red[t * 64] = f4{0, 0, 0, 0};
+
   const bool vec_x = (a.K & 7) == 0;
   const int total_units = a.M << a.x_shift;
   const int units_per_pass = nthr * XUnit<FMT>::XU;
-  XRegs<FMT> xr;
-  if (vec_x) {
-    for (int pass = 1; pass * units_per_pass < total_units; pass++) {
-      x_load<FMT>(xr, a, 0, k_pad, pass, tid, nthr);
-      x_store<FMT>(xr, xs, a, 0, k_pad, pass, tid, nthr);
-    }
-  } else {
-    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
-  }
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
-  if (wave_has_x) x_load<FMT>(xr, a, 0, k_pad, 0, tid, nthr);
-  __builtin_amdgcn_sched_barrier(0);
+  const int chunk_k = RC * REC_K;
 
-  // the head of the weight stream: LR records in flight per wave
-  int pf = min(f0, f_last);  // prefetch cursor (flat index, strip, record), clamped to the wave's last record
-  int ps = (int)((unsigned)pf / (unsigned)a.n_rec), pr = pf - ps * a.n_rec;
-  const int s_first0 = ps, rk0 = pr;
-  // scales of the first strip this wave will finish (the first one that starts inside its piece)
-  const f4 scale0 = load_scales<FMT>(a, min(strip0 + (pr == 0 ? ps : ps + 1), a.n_strips - 1), lane);
-  LaneRec<FMT> ring[LR];
-#pragma unroll
-  for (int q = 0; q < LR; q++) {
-    load_rec<FMT>(ring[q], a, strip0 + ps, pr, lane);
-    if (pf < f_last) {
-      pf++;
-      if (++pr == a.n_rec) pr = 0, ps++;
-    }
-    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
-  }
-
-  if (wave_has_x) x_store<FMT>(xr, xs, a, 0, k_pad, 0, tid, nthr);
-  __syncthreads();
-
-  f4 acc[MT];
-#pragma unroll
-  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
-  // a wave with records starts its prefetch cursor at f0, so (ps, pr) at that moment
-  // were its first strip and the record inside it
-  const int s_first = s_first0;
-  int rk = rk0;  // record inside the current strip
-  int f = f0;
-  f4* my_red = red + (size_t)wave * a.red_slots * MT * 64 + lane;  // this wave's tiles: [slot][MT][64]
-
-  // One record: multiply, refill the ring slot; when the strip (or the wave's piece)
-  // ends here, park the partial tile in LDS.  Nothing in here touches global memory
-  // except the refill, so the ring keeps draining one record at a time.
-  auto step = [&](LaneRec<FMT>& slot) {
-    mac_rec<FMT, MT>(slot, x0 + rk * REC_K, x1 + rk * REC_K, acc);
-    load_rec<FMT>(slot, a, strip0 + ps, pr, lane);
-    if (pf < f_last) {
-      pf++;
-      if (++pr == a.n_rec) pr = 0, ps++;
-    }
-    f++;
-    rk++;
-    if (rk == a.n_rec || f == f1) {
-#pragma unroll
-      for (int i = 0; i < MT; i++) {
-        my_red[i * 64] = acc[i];
-        acc[i] = f4{0, 0, 0, 0};
+  for (int rec_base = 0; rec_base < a.n_rec; rec_base += RC) {
+    // Activations of the phase, in operand order.  Units beyond the first pass (large M)
+    // and unaligned rows are staged by loops that run to completion first; the first
+    // pass is only requested here and stored after the head of the weight stream has
+    // been requested too, so both are in flight together and the stream starts as soon
+    // as its first record lands.  Waves whose units all fall outside skip the pass.
+    if (rec_base > 0) __syncthreads();  // everyone is done with the previous phase's activations
+    const int k0 = rec_base * REC_K;
+    XRegs<FMT> xr;
+    if (vec_x) {
+      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
+        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
+        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
       }
-      my_red += MT * 64;
-      rk = 0;
+    } else {
+      stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
     }
-  };
+    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    __builtin_amdgcn_sched_barrier(0);
 
-  while (f + LR <= f1) {
+    // the head of the weight stream: LR records in flight per wave.  The prefetch cursor
+    // (pair index, strip, record in phase) is clamped to the piece's last pair; records
+    // beyond the end of K (last phase) are redirected to the strip's last record and skipped.
+    const int rec_hi = a.n_rec - 1 - rec_base;  // last valid record of this phase, relative
+    int pp = min(g0, g_last), ps = s_first, pj = j_first;
+    LaneRec<FMT> ring[LR];
 #pragma unroll
     for (int q = 0; q < LR; q++) {
-      step(ring[q]);
-      // keep the refill right behind its record
-      __builtin_amdgcn_sched_barrier(0);
+      load_rec<FMT>(ring[q], a, strip0 + ps, rec_base + min(pj, rec_hi), lane);
+      if (pp < g_last) {
+        pp++;
+        if (++pj == RC) pj = 0, ps++;
+      }
+      __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
     }
-  }
-#pragma unroll
-  for (int q = 0; q < LR - 1; q++)
-    if (f < f1) step(ring[q]);
 
-  // Finish the strips.  The wave that holds a strip's first record owns it: it adds the
+    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+    __syncthreads();
+
+    f4 acc[MT];
+    f4* slot_ptr = my_red;
+#pragma unroll
+    for (int i = 0; i < MT; i++) acc[i] = slot_ptr[i * 64];
+    int g = g0, j = j_first;
+
+    // One pair: multiply, refill the ring slot; where the strip (or the piece) ends, the
+    // tile goes back to its LDS slot and the next strip's tile comes in.  Nothing in
+    // here touches global memory except the refill, so the ring drains one record at a time.
+    auto step = [&](LaneRec<FMT>& slot) {
+      if (j <= rec_hi) mac_rec<FMT, MT>(slot, x0 + j * REC_K, x1 + j * REC_K, acc);
+      load_rec<FMT>(slot, a, strip0 + ps, rec_base + min(pj, rec_hi), lane);
+      if (pp < g_last) {
+        pp++;
+        if (++pj == RC) pj = 0, ps++;
+      }
+      g++;
+      j++;
+      if (j == RC || g == g1) {
+#pragma unroll
+        for (int i = 0; i < MT; i++) slot_ptr[i * 64] = acc[i];
+        if (j == RC) {
+          slot_ptr += MT * 64;
+          j = 0;
+        }
+#pragma unroll
+        for (int i = 0; i < MT; i++) acc[i] = slot_ptr[i * 64];
+      }
+    };
+
+    while (g + LR <= g1) {
+#pragma unroll
+      for (int q = 0; q < LR; q++) {
+        step(ring[q]);
+        // keep the refill right behind its record
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < LR - 1; q++)
+      if (g < g1) step(ring[q]);
+  }
+
+  // Finish the strips.  The wave that holds a strip's first pair owns it: it adds the
   // head tiles (slot 0) of the waves after it whose pieces still lie in that strip, in
   // wave order, and stores.  The tile reads do not depend on each other, so they overlap.
   __syncthreads();
-  if (f1 > f0) {
-    const int s_begin = rk0 == 0 ? s_first : s_first + 1;  // first strip that starts inside this piece
-    for (int s = s_begin; s * a.n_rec < f1; s++) {
-      const int se = (s + 1) * a.n_rec;
+  if (g1 > g0) {
+    const int s_begin = j_first == 0 ? s_first : s_first + 1;  // first strip that starts inside this piece
+    for (int s = s_begin; s * RC < g1; s++) {
+      const int se = (s + 1) * RC;
       f4 sum[MT];
 #pragma unroll
       for (int i = 0; i < MT; i++) sum[i] = red[(((size_t)wave * a.red_slots + (s - s_first)) * MT + i) * 64 + lane];
-      if (se > f1) {  // the strip runs on into the next waves' pieces
+      if (se > g1) {  // the strip runs on into the next waves' pieces
 #pragma unroll
         for (int d = 1; d < 16; d++) {
           const int w2 = min(wave + d, S - 1);
-          const int g0 = w2 * piece_q + min(w2, piece_r), g1 = g0 + piece_q + (w2 < piece_r ? 1 : 0);
-          const bool take = wave + d < S && g0 < se && g1 > g0;
+          const int h0 = w2 * piece_q + min(w2, piece_r), h1 = h0 + piece_q + (w2 < piece_r ? 1 : 0);
+          const bool take = wave + d < S && h0 < se && h1 > h0;
 #pragma unroll
           for (int i = 0; i < MT; i++) {
             // selected, not multiplied: a tile that is not taken may be uninitialised LDS
@@ -737,36 +751,45 @@ constexpr int kStreamLdsMax = 150 * 1024;  // of the 160 KiB a workgroup may use
 
 struct StreamPlan {
   bool ok;
-  int S, lr, spw, grid, x_shift, x_stride, x_region, red_slots;
+  int S, lr, spw, grid, rc, x_shift, x_stride, x_region, red_slots;
   size_t lds;
 };
 
 // Launch shape of the streaming kernel: one workgroup of 16 wavefronts per CU, each
-// owning an equal run of whole strips.  Not applicable (ok = false) when the staged
-// activations M x K do not fit in LDS.
+// owning an equal run of whole strips; K is walked in as few phases as the LDS allows
+// (activations of a phase: M x rc records; plus the waves' tile slots).
 StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
   StreamPlan p;
   const int mt = M > 16 ? 2 : 1;
   // strips per workgroup: one resident round, but at most 32 (a wave parks one tile per strip it touches)
   p.spw = (int)std::min<int64_t>(32, (n_strips + kNumCU - 1) / kNumCU);
   p.grid = (int)((n_strips + p.spw - 1) / p.spw);
-  const int64_t F = (int64_t)p.spw * n_rec;
-  p.S = (int)std::min<int64_t>(16, std::max<int64_t>(1, F));
-  const int per_wave = (int)(F / p.S);
-  // measured on the Llama-8B/70B shapes: deeper rings only lengthen the drain at the end of the stream
-  const int lr_max = fmt == FMT_FP16 ? 2 : 4;  // the baseline's records are four times larger
-  p.lr = lr_max;
-  while (p.lr > 2 && p.lr > per_wave) p.lr /= 2;
-  const int k_pad = n_rec * rec_k;
-  const int units = k_pad / (fmt == FMT_FP533 ? 24 : 8);
-  p.x_shift = 0;
-  while ((1 << p.x_shift) < units) p.x_shift++;
-  p.x_stride = k_pad + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
-  p.x_region = M * p.x_stride;
-  const int per_wave_max = (int)((F + p.S - 1) / p.S);
-  p.red_slots = (per_wave_max - 1) / n_rec + 2;
-  p.lds = (size_t)p.x_region * 2 + (size_t)p.S * p.red_slots * mt * 64 * 16 + (size_t)p.S * 4;
-  p.ok = p.lds <= (size_t)kStreamLdsMax;
+  p.ok = false;
+  for (int n_phase = 1; n_phase <= n_rec; n_phase++) {
+    const int rc = (n_rec + n_phase - 1) / n_phase;
+    if (n_phase > 1 && rc == (n_rec + n_phase - 2) / (n_phase - 1)) continue;  // same rc as before
+    const int64_t P = (int64_t)p.spw * rc;
+    const int S = (int)std::min<int64_t>(16, std::max<int64_t>(1, P));
+    const int per_wave_max = (int)((P + S - 1) / S);
+    const int slots = (per_wave_max - 1) / rc + 2;
+    const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+    const size_t lds = (size_t)M * x_stride * 2 + (size_t)S * slots * mt * 64 * 16;
+    if (lds > (size_t)kStreamLdsMax) continue;
+    p.ok = true;
+    p.rc = rc;
+    p.S = S;
+    p.red_slots = slots;
+    p.x_stride = x_stride;
+    p.x_region = M * x_stride;
+    p.lds = lds;
+    // measured on the Llama-8B/70B shapes: deeper rings only lengthen the drain at the end of the stream
+    p.lr = fmt == FMT_FP16 ? 2 : 4;  // the baseline's records are four times larger
+    while (p.lr > 2 && p.lr > per_wave_max) p.lr /= 2;
+    const int units = rc * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    p.x_shift = 0;
+    while ((1 << p.x_shift) < units) p.x_shift++;
+    break;
+  }
   return p;
 }
 
@@ -843,8 +866,9 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.x_shift = sp.x_shift;
     a.spw = sp.spw;
     a.red_slots = sp.red_slots;
-    a.piece_q = (int)(((int64_t)sp.spw * n_rec) / sp.S);
-    a.piece_r = (int)(((int64_t)sp.spw * n_rec) % sp.S);
+    a.piece_q = (int)(((int64_t)sp.spw * sp.rc) / sp.S);
+    a.piece_r = (int)(((int64_t)sp.spw * sp.rc) % sp.S);
+    a.rc = sp.rc;
     return M <= 16 ? launch_by_ring<FMT, 1>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st)
                    : launch_by_ring<FMT, 2>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st);
   }
@@ -856,6 +880,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.spw = 1;
   a.red_slots = 0;
   a.piece_q = a.piece_r = 0;
+  a.rc = 0;
   return M <= 16 ? launch_by_ring<FMT, 1>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st)
                  : launch_by_ring<FMT, 2>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st);
 }

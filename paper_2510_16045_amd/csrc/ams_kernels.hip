@@ -404,19 +404,30 @@ __device__ __forceinline__ void store_tile(const f4 t[MT], const LinearArgs& a, 
   }
 }
 
-// fp32 multipliers s_n * 2^14 of the four output channels a lane holds of a strip's tile
+// fp16 bits of the scales of the four output channels a lane holds of a strip's tile
+struct ScaleBits {
+  uint16_t b[4];
+};
 template <int FMT>
-__device__ __forceinline__ f4 load_scales(const LinearArgs& a, int strip, int lane) {
-  f4 sc = {1.0f, 1.0f, 1.0f, 1.0f};
+__device__ __forceinline__ ScaleBits load_scale_bits(const LinearArgs& a, int strip, int lane) {
+  ScaleBits sb = {{0x3C00, 0x3C00, 0x3C00, 0x3C00}};
   if constexpr (FMT != FMT_FP16) {
     const int n0 = strip * 16 + 4 * (lane >> 4);
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int n = min(n0 + r, a.N - 1);  // clamped: rows beyond N are never stored
-      sc[r] = (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
-    }
+    for (int r = 0; r < 4; r++) sb.b[r] = a.scales[min(n0 + r, a.N - 1)];  // clamped: rows beyond N are never stored
   }
+  return sb;
+}
+// fp32 multipliers s_n * 2^14 (the baseline's "scales" are 1: its bits are 1.0 and no 2^14 is owed)
+__device__ __forceinline__ f4 scales_from_bits(const ScaleBits& sb, float mul = kTwo14) {
+  f4 sc;
+#pragma unroll
+  for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, sb.b[r]) * mul;
   return sc;
+}
+template <int FMT>
+__device__ __forceinline__ f4 load_scales(const LinearArgs& a, int strip, int lane) {
+  return scales_from_bits(load_scale_bits<FMT>(a, strip, lane), FMT == FMT_FP16 ? 1.0f : kTwo14);
 }
 
 // Multiply a finished 16x16 tile (C[i][j]: lane = j + 16*(i/4), register i%4) by the scales, convert, store.
@@ -491,6 +502,11 @@ template <int FMT, int MT, int LR>
 __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
+  // All kernel arguments are pulled in at once: fetched piecemeal where they are first used,
+  // each batch would be one more trip to memory in front of the first weight load.
+  asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.red_slots), "s"(a.piece_q), "s"(a.piece_r),
+               "s"(a.rc));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = nthr >> 6;
@@ -507,8 +523,9 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   }
   const int g0 = wave * piece_q + min(wave, piece_r), g1 = g0 + piece_q + (wave < piece_r ? 1 : 0);
   const int g_last = max(g1 - 1, 0);
-  const int s_first = (int)((unsigned)min(g0, g_last) / (unsigned)RC);  // strip of the piece's first pair
-  const int j_first = min(g0, g_last) - s_first * RC;                   // its record inside the phase
+  // strip of the piece's first pair and its record inside the phase
+  const int s_first = (int)((unsigned)min(g0, g_last) / (unsigned)RC);
+  const int j_first = min(g0, g_last) - s_first * RC;
   _Float16* xs = (_Float16*)smem;
   f4* red = (f4*)(smem + (size_t)a.x_region * 2);  // [S][red_slots][MT][64]
   f4* const my_red = red + (size_t)wave * a.red_slots * MT * 64 + lane;  // this wave's tiles: [slot][MT][64]
@@ -518,15 +535,16 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
   const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
 
-  // scales of the first strip this wave will finish (the first one that starts inside its piece)
-  const f4 scale0 = load_scales<FMT>(a, min(strip0 + (j_first == 0 ? s_first : s_first + 1), a.n_strips - 1), lane);
-  for (int t = 0; t < a.red_slots * MT; t++) my_red[t * 64] = f4{0, 0, 0, 0};
-
   const bool vec_x = (a.K & 7) == 0;
   const int total_units = a.M << a.x_shift;
   const int units_per_pass = nthr * XUnit<FMT>::XU;
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
   const int chunk_k = RC * REC_K;
+  // Scales of the first strip this wave will finish (the first one that starts inside its
+  // piece): requested before everything else and left as raw fp16 bits until the epilogue,
+  // so that nothing waits on them while the weight stream is being set up.
+  const ScaleBits scale0_bits = load_scale_bits<FMT>(a, min(strip0 + (j_first == 0 ? s_first : s_first + 1), a.n_strips - 1), lane);
+  __builtin_amdgcn_sched_barrier(0);
 
   for (int rec_base = 0; rec_base < a.n_rec; rec_base += RC) {
     // Activations of the phase, in operand order.  Units beyond the first pass (large M)
@@ -564,6 +582,10 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
       __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
     }
 
+    if (rec_base == 0) {
+      // set-up that nothing above needs, done while the first loads are in flight: this wave's tile slots cleared
+      for (int t = 0; t < a.red_slots * MT; t++) my_red[t * 64] = f4{0, 0, 0, 0};
+    }
     if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
     __syncthreads();
 
@@ -621,21 +643,29 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
       f4 sum[MT];
 #pragma unroll
       for (int i = 0; i < MT; i++) sum[i] = red[(((size_t)wave * a.red_slots + (s - s_first)) * MT + i) * 64 + lane];
-      if (se > g1) {  // the strip runs on into the next waves' pieces
+      if (se > g1) {  // the strip runs on into the pieces of the next nf waves
+        int nf = 0;
+        for (int w2 = wave + 1, h0 = g1; w2 < S && h0 < se; w2++) {
+          const int len = piece_q + (w2 < piece_r ? 1 : 0);
+          if (len == 0) break;
+          h0 += len;
+          nf++;
+        }
+        const f4* follower = red + (size_t)wave * a.red_slots * MT * 64 + lane;  // slot 0 of this wave; followers are whole waves further
+        const int wave_stride = a.red_slots * MT * 64;
 #pragma unroll
         for (int d = 1; d < 16; d++) {
-          const int w2 = min(wave + d, S - 1);
-          const int h0 = w2 * piece_q + min(w2, piece_r), h1 = h0 + piece_q + (w2 < piece_r ? 1 : 0);
-          const bool take = wave + d < S && h0 < se && h1 > h0;
+          // reads are independent and unconditional (inside the tile area: wave index clamped);
+          // selected, not multiplied: a tile that is not taken may be uninitialised LDS
+          const f4* t = follower + min(d, S - 1 - wave) * wave_stride;
 #pragma unroll
           for (int i = 0; i < MT; i++) {
-            // selected, not multiplied: a tile that is not taken may be uninitialised LDS
-            const f4 t = red[(((size_t)w2 * a.red_slots + 0) * MT + i) * 64 + lane];
-            sum[i] += take ? t : f4{0, 0, 0, 0};
+            const f4 v = t[i * 64];
+            sum[i] += d <= nf ? v : f4{0, 0, 0, 0};
           }
         }
       }
-      store_tile_scaled<MT>(sum, s == s_begin ? scale0 : load_scales<FMT>(a, strip0 + s, lane), a, strip0 + s, lane);
+      store_tile_scaled<MT>(sum, s == s_begin ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip0 + s, lane), a, strip0 + s, lane);
     }
   }
 }

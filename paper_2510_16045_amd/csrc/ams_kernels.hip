@@ -670,6 +670,160 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   }
 }
 
+// The sweeping Linear.  Strips are dealt to the workgroups round robin (workgroup g owns
+// strips g, g + G, g + 2G, ...), and inside a workgroup the records of its strips, taken
+// as one list in that order, are dealt to the S wavefronts record by record.  At any
+// moment a workgroup therefore reads one contiguous run of S * LR records, and the whole
+// grid reads a window of G neighbouring strips that moves through the matrix front to
+// back: the order the memory system serves fastest (measured with bare read kernels, this
+// beats per-wavefront contiguous pieces by 15-20 % on the Llama shapes, and two records in
+// flight per wave beat four).  Every wave meets every strip of its workgroup, so it parks
+// one partial 16x16 tile per strip in LDS (only the lanes of existing activation rows);
+// after one barrier the strips are finished one per wave: the S tiles added in wave
+// order, scaled, converted, stored.  The activations (all of K) are staged once per
+// workgroup in LDS in operand order.  The grid is one resident round.
+template <int FMT, int MT, int LR>
+__global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int REC_K = Fmt<FMT>::REC_K;
+  asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw));
+  const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int S = nthr >> 6;
+  const int G = gridDim.x, g = blockIdx.x;
+  const int ns = (a.n_strips - g + G - 1) / G;  // strips of this workgroup (>= 1)
+  const int n_rec = a.n_rec;
+  const int total = ns * n_rec;                                 // records of this workgroup
+  const int cnt = wave < total ? (total - wave + S - 1) / S : 0;  // records of this wave
+  const int mc = min(a.M, 16);  // activation rows of an MFMA tile that exist
+  _Float16* xs = (_Float16*)smem;
+  f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][S][MT][4 K-quarters][mc]
+  const int m_lo = lane & 15, kq = lane >> 4;
+  const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
+  // lanes whose activation row does not exist read row 0: they only feed output columns never stored
+  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
+  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
+  const int part_f4 = MT * 4 * mc;  // f4 per parked tile
+  f4* const my_part = parts + (size_t)wave * part_f4 + kq * mc + m_lo;  // this wave's tile of local strip 0
+
+  const bool vec_x = (a.K & 7) == 0;
+  const int total_units = a.M << a.x_shift;
+  const int units_per_pass = nthr * XUnit<FMT>::XU;
+  const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
+  const int k_pad = n_rec * REC_K;
+  // Scales of the first strip this wave finishes: requested first, kept as raw bits until the epilogue.
+  const ScaleBits scale0_bits = load_scale_bits<FMT>(a, min(g + min(wave, ns - 1) * G, a.n_strips - 1), lane);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Activations: units beyond the first pass (large M) and unaligned rows are staged by loops
+  // that run to completion; the first pass is only requested here and stored behind the
+  // head of the weight stream, so both are in flight together.
+  XRegs<FMT> xr;
+  if (vec_x) {
+    for (int pass = 1; pass * units_per_pass < total_units; pass++) {
+      x_load<FMT>(xr, a, 0, k_pad, pass, tid, nthr);
+      x_store<FMT>(xr, xs, a, 0, k_pad, pass, tid, nthr);
+    }
+  } else {
+    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
+  }
+  if (wave_has_x) x_load<FMT>(xr, a, 0, k_pad, 0, tid, nthr);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Head of the weight stream.  The prefetch cursor (position in the list, local strip,
+  // record) stops at the wave's last record; a wave without records reads record 0.
+  int pf = wave < total ? wave : 0, pj = 0, pr = pf;
+  while (pr >= n_rec) pr -= n_rec, pj++;
+  const int cj0 = pj, cr0 = pr;
+  // LR records are in flight while a record is being restored: the ring has one slot more,
+  // and a step first requests the record LR places ahead into the slot freed by the step
+  // before, then works on its own (a refill into the slot being read would have to wait
+  // until the restoration has consumed it).
+  constexpr int RS = LR + 1;
+  LaneRec<FMT> ring[RS];
+  auto request = [&](LaneRec<FMT>& slot) {
+    load_rec<FMT>(slot, a, g + pj * G, pr, lane);
+    if (pf + S < total) {
+      pf += S, pr += S;
+      while (pr >= n_rec) pr -= n_rec, pj++;
+    }
+  };
+#pragma unroll
+  for (int q = 0; q < LR; q++) {
+    request(ring[q]);
+    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
+  }
+
+  // while those are in flight: every tile slot cleared (a wave need not meet every strip when a
+  // strip has fewer records than the workgroup has waves)
+  for (int i = tid; i < ns * S * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
+  if (wave_has_x) x_store<FMT>(xr, xs, a, 0, k_pad, 0, tid, nthr);
+  __syncthreads();
+
+  f4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
+  int cj = cj0, cr = cr0;  // local strip and record of the record being multiplied
+  bool pending = false;    // acc holds products that are not parked yet
+
+  auto park = [&]() {
+    if (m_lo < mc) {
+      f4* t = my_part + (size_t)cj * S * part_f4;
+#pragma unroll
+      for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
+    }
+#pragma unroll
+    for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
+  };
+  // One record: request the one LR ahead, multiply, move on by S records; where that leaves
+  // the strip, the tile is parked.  Only the request touches global memory.
+  auto step = [&](LaneRec<FMT>& slot, LaneRec<FMT>& free_slot) {
+    request(free_slot);
+    __builtin_amdgcn_sched_barrier(0);
+    mac_rec<FMT, MT>(slot, x0 + cr * REC_K, x1 + cr * REC_K, acc);
+    pending = true;
+    cr += S;
+    if (cr >= n_rec) {
+      park();
+      pending = false;
+      do {
+        cr -= n_rec, cj++;
+      } while (cr >= n_rec);
+    }
+  };
+
+  int i = 0;
+  for (; i + RS <= cnt; i += RS) {
+#pragma unroll
+    for (int q = 0; q < RS; q++) {
+      step(ring[q], ring[(q + LR) % RS]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < RS - 1; q++)
+    if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
+  if (pending) park();
+
+  // Finish the strips, one per wave: the S parked tiles added in wave order.
+  __syncthreads();
+  for (int j = wave; j < ns; j += S) {
+    f4 sum[MT];
+#pragma unroll
+    for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+    if (m_lo < mc) {
+      const f4* t0 = parts + (size_t)j * S * part_f4 + kq * mc + m_lo;
+      for (int w = 0; w < S; w++) {
+#pragma unroll
+        for (int t = 0; t < MT; t++) sum[t] += t0[(size_t)w * part_f4 + t * 4 * mc];
+      }
+    }
+    const int strip = g + j * G;
+    store_tile_scaled<MT>(sum, j == wave ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip, lane), a, strip, lane);
+  }
+}
+
 // Restore a whole packed matrix to row-major fp16: one wavefront per record.
 template <int FMT>
 __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const uint16_t* scales, uint16_t* out, int N, int K,
@@ -823,6 +977,32 @@ StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec
   return p;
 }
 
+struct SweepPlan {
+  bool ok;
+  int S, lr, spw, grid, x_shift, x_stride, x_region;
+  size_t lds;
+};
+
+// Launch shape of the sweeping kernel: one resident round of workgroups of up to 16
+// wavefronts, all of K staged in LDS plus one parked tile per (strip, wave).
+SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
+  SweepPlan p;
+  const int mt = M > 16 ? 2 : 1;
+  const int mc = std::min(M, 16);
+  p.spw = (int)((n_strips + kNumCU - 1) / kNumCU);
+  p.grid = (int)((n_strips + p.spw - 1) / p.spw);
+  p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * n_rec);
+  p.x_stride = n_rec * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+  p.x_region = M * p.x_stride;
+  p.lds = (size_t)p.x_region * 2 + (size_t)p.spw * p.S * mt * 4 * mc * 16;
+  p.ok = n_strips <= (int64_t)kNumCU * 64 && p.lds <= (size_t)kStreamLdsMax;
+  p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
+  const int units = n_rec * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+  p.x_shift = 0;
+  while ((1 << p.x_shift) < units) p.x_shift++;
+  return p;
+}
+
 // Kernels that use more than 64 KiB of dynamic LDS must have their limit raised first;
 // that is a per-function, per-device property, remembered here so it is done once.
 bool raise_lds_limit(const void* kern) {
@@ -849,9 +1029,17 @@ int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hip
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
+enum KernelKind { kSweep, kStream, kPhase };
+
 template <int FMT, int MT>
-int launch_by_ring(bool stream, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
-  if (stream) {
+int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  if (kind == kSweep) {
+    switch (lr) {
+      case 4: if constexpr (FMT != FMT_FP16) return launch(sweep_kernel<FMT, MT, 4>, a, grid, S, lds, st); break;
+      case 2: return launch(sweep_kernel<FMT, MT, 2>, a, grid, S, lds, st);
+      case 1: return launch(sweep_kernel<FMT, MT, 1>, a, grid, S, lds, st);
+    }
+  } else if (kind == kStream) {
     switch (lr) {
       case 8: if constexpr (FMT != FMT_FP16) return launch(stream_kernel<FMT, MT, 8>, a, grid, S, lds, st); break;
       case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
@@ -888,6 +1076,19 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.n_rec = n_rec;
   a.n_strips = (int)n_strips;
   hipStream_t st = (hipStream_t)stream;
+  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K);
+  if (wp.ok) {
+    a.x_stride = wp.x_stride;
+    a.x_region = wp.x_region;
+    a.x_phase = 0;
+    a.x_shift = wp.x_shift;
+    a.spw = wp.spw;
+    a.red_slots = 0;
+    a.piece_q = a.piece_r = 0;
+    a.rc = n_rec;
+    return M <= 16 ? launch_by_ring<FMT, 1>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st)
+                   : launch_by_ring<FMT, 2>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st);
+  }
   const StreamPlan sp = make_stream_plan(FMT, M, n_strips, n_rec, REC_K);
   if (sp.ok) {
     a.x_stride = sp.x_stride;
@@ -899,8 +1100,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.piece_q = (int)(((int64_t)sp.spw * sp.rc) / sp.S);
     a.piece_r = (int)(((int64_t)sp.spw * sp.rc) % sp.S);
     a.rc = sp.rc;
-    return M <= 16 ? launch_by_ring<FMT, 1>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st)
-                   : launch_by_ring<FMT, 2>(true, sp.lr, a, sp.grid, sp.S, sp.lds, st);
+    return M <= 16 ? launch_by_ring<FMT, 1>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st)
+                   : launch_by_ring<FMT, 2>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st);
   }
   const Plan p = make_plan(FMT, M, n_strips, n_rec, REC_K);
   a.x_stride = p.x_stride;
@@ -911,8 +1112,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.red_slots = 0;
   a.piece_q = a.piece_r = 0;
   a.rc = 0;
-  return M <= 16 ? launch_by_ring<FMT, 1>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st)
-                 : launch_by_ring<FMT, 2>(false, p.lr, a, (unsigned)n_strips, p.S, p.lds, st);
+  return M <= 16 ? launch_by_ring<FMT, 1>(kPhase, p.lr, a, (unsigned)n_strips, p.S, p.lds, st)
+                 : launch_by_ring<FMT, 2>(kPhase, p.lr, a, (unsigned)n_strips, p.S, p.lds, st);
 }
 
 }  // namespace

@@ -31,8 +31,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
-# by what the same counter reads for a 256 MiB device copy (profiles/stream_kernel_gate_up_fp533_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77604 + 56) * 1024}
+# by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
+MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77689 + 56) * 1024}
 FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2"}
 
 
@@ -265,7 +265,7 @@ def main():
     t_dom = time_launches(torch, lambda i: ams.ams_linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, out=ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
     roofline = {
-        "bound": "hbm", "kernel": f"stream_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
+        "bound": "hbm", "kernel": f"sweep_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes,
         "traffic": MEASURED_TRAFFIC_BYTES.get((dl.name, dom["fmt"], M)) if args.layers == "8b" else None,

@@ -5,10 +5,12 @@
 // Every lane loads its 16-byte chunk of a record with one dwordx4 (a record is one
 // contiguous 1 KiB access per wavefront), restores the fp16 pairs in registers and feeds
 // them as the A operand of v_mfma_f32_16x16x32_f16; the activations are staged in LDS in
-// the operand order the restoration produces.  Two kernels share these pieces:
-// stream_kernel (one resident round of workgroups, equal contiguous record pieces per
-// wavefront, activations shared by the workgroup) and phase_kernel (one workgroup per
-// strip, activations staged per wavefront in phases, for M x K too large for LDS).
+// the operand order the restoration produces.  Three kernels share these pieces:
+// sweep_kernel (the default: one resident round of workgroups, strips dealt round robin,
+// records dealt to the wavefronts one by one, so the grid reads one moving window),
+// stream_kernel (equal contiguous record pieces per wavefront; for shapes whose parked
+// tiles would not fit the sweep's LDS) and phase_kernel (one workgroup per strip,
+// activations staged per wavefront in phases; the last fallback).
 // Partial tiles are combined through LDS: no global workspace, no atomics.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -119,8 +121,10 @@ struct LinearArgs {
   int rc;                // stream kernel: records per strip in one phase of K
 };
 
-// Unconditional loads of one record (rec must be a valid record of the strip).
-template <int FMT>
+// Unconditional loads of one record (rec must be a valid record of the strip).  NT: packed
+// records bypass the caches' retention (they are read once); matrices small enough to
+// sit in the last-level cache between calls are better served by ordinary loads.
+template <int FMT, bool NT = true>
 __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, int strip, int rec, int lane) {
   if constexpr (FMT == FMT_FP16) {
     // rows beyond N and K-chunks beyond K are redirected to the matrix's first 16 bytes
@@ -138,8 +142,13 @@ __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, i
     }
   } else {
     const uint8_t* base = a.W + ((size_t)strip * a.n_rec + rec) * Fmt<FMT>::REC_BYTES;
-    r.w = __builtin_nontemporal_load((const u4*)(base + lane * 16));
-    if constexpr (FMT == FMT_FP425) r.t = __builtin_nontemporal_load(base + 1024 + lane);
+    if constexpr (NT) {
+      r.w = __builtin_nontemporal_load((const u4*)(base + lane * 16));
+      if constexpr (FMT == FMT_FP425) r.t = __builtin_nontemporal_load(base + 1024 + lane);
+    } else {
+      r.w = *(const u4*)(base + lane * 16);
+      if constexpr (FMT == FMT_FP425) r.t = base[1024 + lane];
+    }
   }
 }
 
@@ -680,22 +689,22 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
 // flight per wave beat four).  Every wave meets every strip of its workgroup, so it parks
 // one partial 16x16 tile per strip in LDS (only the lanes of existing activation rows);
 // after one barrier the strips are finished one per wave: the S tiles added in wave
-// order, scaled, converted, stored.  The activations (all of K) are staged once per
-// workgroup in LDS in operand order.  The grid is one resident round.
-template <int FMT, int MT, int LR>
+// order, scaled, converted, stored.  The activations are staged once per workgroup in LDS
+// in operand order; when M x K does not fit, K is walked in phases of rc records per strip
+// and the parked tiles accumulate over the phases.  The grid is one resident round.
+template <int FMT, int MT, int LR, bool NT>
 __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
-               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw));
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = nthr >> 6;
   const int G = gridDim.x, g = blockIdx.x;
   const int ns = (a.n_strips - g + G - 1) / G;  // strips of this workgroup (>= 1)
-  const int n_rec = a.n_rec;
-  const int total = ns * n_rec;                                 // records of this workgroup
-  const int cnt = wave < total ? (total - wave + S - 1) / S : 0;  // records of this wave
+  const int RC = a.rc;                          // records per strip in one phase of K
+  const bool one_phase = RC >= a.n_rec;
   const int mc = min(a.M, 16);  // activation rows of an MFMA tile that exist
   _Float16* xs = (_Float16*)smem;
   f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][S][MT][4 K-quarters][mc]
@@ -711,100 +720,114 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   const int total_units = a.M << a.x_shift;
   const int units_per_pass = nthr * XUnit<FMT>::XU;
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
-  const int k_pad = n_rec * REC_K;
+  const int chunk_k = RC * REC_K;
   // Scales of the first strip this wave finishes: requested first, kept as raw bits until the epilogue.
   const ScaleBits scale0_bits = load_scale_bits<FMT>(a, min(g + min(wave, ns - 1) * G, a.n_strips - 1), lane);
   __builtin_amdgcn_sched_barrier(0);
 
-  // Activations: units beyond the first pass (large M) and unaligned rows are staged by loops
-  // that run to completion; the first pass is only requested here and stored behind the
-  // head of the weight stream, so both are in flight together.
-  XRegs<FMT> xr;
-  if (vec_x) {
-    for (int pass = 1; pass * units_per_pass < total_units; pass++) {
-      x_load<FMT>(xr, a, 0, k_pad, pass, tid, nthr);
-      x_store<FMT>(xr, xs, a, 0, k_pad, pass, tid, nthr);
+  // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
+  for (int rec_base = 0; rec_base < a.n_rec; rec_base += RC) {
+    const int n_rec = min(RC, a.n_rec - rec_base);                // records per strip in this phase
+    const int total = ns * n_rec;                                 // records of this workgroup
+    const int cnt = wave < total ? (total - wave + S - 1) / S : 0;  // records of this wave
+    if (rec_base > 0) __syncthreads();  // everyone is done with the previous phase's activations
+    const int k0 = rec_base * REC_K;
+
+    // Activations: units beyond the first pass (large M) and unaligned rows are staged by loops
+    // that run to completion; the first pass is only requested here and stored behind the
+    // head of the weight stream, so both are in flight together.
+    XRegs<FMT> xr;
+    if (vec_x) {
+      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
+        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
+        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
+      }
+    } else {
+      stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
     }
-  } else {
-    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
-  }
-  if (wave_has_x) x_load<FMT>(xr, a, 0, k_pad, 0, tid, nthr);
-  __builtin_amdgcn_sched_barrier(0);
+    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    __builtin_amdgcn_sched_barrier(0);
 
-  // Head of the weight stream.  The prefetch cursor (position in the list, local strip,
-  // record) stops at the wave's last record; a wave without records reads record 0.
-  int pf = wave < total ? wave : 0, pj = 0, pr = pf;
-  while (pr >= n_rec) pr -= n_rec, pj++;
-  const int cj0 = pj, cr0 = pr;
-  // LR records are in flight while a record is being restored: the ring has one slot more,
-  // and a step first requests the record LR places ahead into the slot freed by the step
-  // before, then works on its own (a refill into the slot being read would have to wait
-  // until the restoration has consumed it).
-  constexpr int RS = LR + 1;
-  LaneRec<FMT> ring[RS];
-  auto request = [&](LaneRec<FMT>& slot) {
-    load_rec<FMT>(slot, a, g + pj * G, pr, lane);
-    if (pf + S < total) {
-      pf += S, pr += S;
-      while (pr >= n_rec) pr -= n_rec, pj++;
+    // Head of the weight stream.  The prefetch cursor (position in the list, local strip,
+    // record) stops at the wave's last record; a wave without records reads record 0.
+    int pf = wave < total ? wave : 0, pj = 0, pr = pf;
+    while (pr >= n_rec) pr -= n_rec, pj++;
+    int cj = pj, cr = pr;  // local strip and record (inside the phase) of the record being multiplied
+    // LR records are in flight while a record is being restored: the ring has one slot more,
+    // and a step first requests the record LR places ahead into the slot freed by the step
+    // before, then works on its own (a refill into the slot being read would have to wait
+    // until the restoration has consumed it).
+    constexpr int RS = LR + 1;
+    LaneRec<FMT> ring[RS];
+    auto request = [&](LaneRec<FMT>& slot) {
+      load_rec<FMT, NT>(slot, a, g + pj * G, rec_base + pr, lane);
+      if (pf + S < total) {
+        pf += S, pr += S;
+        while (pr >= n_rec) pr -= n_rec, pj++;
+      }
+    };
+#pragma unroll
+    for (int q = 0; q < LR; q++) {
+      request(ring[q]);
+      __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
     }
-  };
-#pragma unroll
-  for (int q = 0; q < LR; q++) {
-    request(ring[q]);
-    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
-  }
 
-  // while those are in flight: every tile slot cleared (a wave need not meet every strip when a
-  // strip has fewer records than the workgroup has waves)
-  for (int i = tid; i < ns * S * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
-  if (wave_has_x) x_store<FMT>(xr, xs, a, 0, k_pad, 0, tid, nthr);
-  __syncthreads();
+    // while those are in flight: every tile slot cleared (a wave need not meet every strip when a
+    // strip has fewer records than the workgroup has waves)
+    if (rec_base == 0)
+      for (int i = tid; i < ns * S * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
+    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+    __syncthreads();
 
-  f4 acc[MT];
-#pragma unroll
-  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
-  int cj = cj0, cr = cr0;  // local strip and record of the record being multiplied
-  bool pending = false;    // acc holds products that are not parked yet
-
-  auto park = [&]() {
-    if (m_lo < mc) {
-      f4* t = my_part + (size_t)cj * S * part_f4;
-#pragma unroll
-      for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
-    }
+    f4 acc[MT];
 #pragma unroll
     for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
-  };
-  // One record: request the one LR ahead, multiply, move on by S records; where that leaves
-  // the strip, the tile is parked.  Only the request touches global memory.
-  auto step = [&](LaneRec<FMT>& slot, LaneRec<FMT>& free_slot) {
-    request(free_slot);
-    __builtin_amdgcn_sched_barrier(0);
-    mac_rec<FMT, MT>(slot, x0 + cr * REC_K, x1 + cr * REC_K, acc);
-    pending = true;
-    cr += S;
-    if (cr >= n_rec) {
-      park();
-      pending = false;
-      do {
-        cr -= n_rec, cj++;
-      } while (cr >= n_rec);
-    }
-  };
+    bool pending = false;  // acc holds products that are not parked yet
 
-  int i = 0;
-  for (; i + RS <= cnt; i += RS) {
+    auto park = [&]() {
+      if (m_lo < mc) {
+        f4* t = my_part + (size_t)cj * S * part_f4;
+        if (one_phase) {
 #pragma unroll
-    for (int q = 0; q < RS; q++) {
-      step(ring[q], ring[(q + LR) % RS]);
+          for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
+        } else {  // the slot belongs to this wave alone: a plain read-add-write
+#pragma unroll
+          for (int i = 0; i < MT; i++) t[i * 4 * mc] += acc[i];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
+    };
+    // One record: request the one LR ahead, multiply, move on by S records; where that leaves
+    // the strip, the tile is parked.  Only the request touches global memory.
+    auto step = [&](LaneRec<FMT>& slot, LaneRec<FMT>& free_slot) {
+      request(free_slot);
       __builtin_amdgcn_sched_barrier(0);
-    }
-  }
+      mac_rec<FMT, MT>(slot, x0 + cr * REC_K, x1 + cr * REC_K, acc);
+      pending = true;
+      cr += S;
+      if (cr >= n_rec) {
+        park();
+        pending = false;
+        do {
+          cr -= n_rec, cj++;
+        } while (cr >= n_rec);
+      }
+    };
+
+    int i = 0;
+    for (; i + RS <= cnt; i += RS) {
 #pragma unroll
-  for (int q = 0; q < RS - 1; q++)
-    if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
-  if (pending) park();
+      for (int q = 0; q < RS; q++) {
+        step(ring[q], ring[(q + LR) % RS]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < RS - 1; q++)
+      if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
+    if (pending) park();
+  }
 
   // Finish the strips, one per wave: the S parked tiles added in wave order.
   __syncthreads();
@@ -979,27 +1002,41 @@ StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec
 
 struct SweepPlan {
   bool ok;
-  int S, lr, spw, grid, x_shift, x_stride, x_region;
+  int S, lr, spw, grid, rc, x_shift, x_stride, x_region;
   size_t lds;
 };
 
 // Launch shape of the sweeping kernel: one resident round of workgroups of up to 16
-// wavefronts, all of K staged in LDS plus one parked tile per (strip, wave).
+// wavefronts; LDS holds one parked tile per (strip, wave) and the activations of one
+// phase of K, in as few phases as fit.
 SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
   SweepPlan p;
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
+  p.ok = false;
+  if (n_strips > (int64_t)kNumCU * 64) return p;
   p.spw = (int)((n_strips + kNumCU - 1) / kNumCU);
   p.grid = (int)((n_strips + p.spw - 1) / p.spw);
   p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * n_rec);
-  p.x_stride = n_rec * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
-  p.x_region = M * p.x_stride;
-  p.lds = (size_t)p.x_region * 2 + (size_t)p.spw * p.S * mt * 4 * mc * 16;
-  p.ok = n_strips <= (int64_t)kNumCU * 64 && p.lds <= (size_t)kStreamLdsMax;
   p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
-  const int units = n_rec * rec_k / (fmt == FMT_FP533 ? 24 : 8);
-  p.x_shift = 0;
-  while ((1 << p.x_shift) < units) p.x_shift++;
+  const size_t parts = (size_t)p.spw * p.S * mt * 4 * mc * 16;
+  for (int n_phase = 1; n_phase <= 8 && n_phase <= n_rec; n_phase++) {
+    const int rc = (n_rec + n_phase - 1) / n_phase;
+    const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+    const size_t lds = (size_t)M * x_stride * 2 + parts;
+    if (lds > (size_t)kStreamLdsMax) continue;
+    // measured: with many parked tiles and more than two phases the contiguous-piece kernel is faster
+    if (n_phase > 2 && parts > 32 * 1024) break;
+    p.ok = true;
+    p.rc = rc;
+    p.x_stride = x_stride;
+    p.x_region = M * x_stride;
+    p.lds = lds;
+    const int units = rc * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    p.x_shift = 0;
+    while ((1 << p.x_shift) < units) p.x_shift++;
+    break;
+  }
   return p;
 }
 
@@ -1029,15 +1066,16 @@ int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hip
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
-enum KernelKind { kSweep, kStream, kPhase };
+enum KernelKind { kSweep, kSweepCached, kStream, kPhase };
 
 template <int FMT, int MT>
 int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
-  if (kind == kSweep) {
-    switch (lr) {
-      case 4: if constexpr (FMT != FMT_FP16) return launch(sweep_kernel<FMT, MT, 4>, a, grid, S, lds, st); break;
-      case 2: return launch(sweep_kernel<FMT, MT, 2>, a, grid, S, lds, st);
-      case 1: return launch(sweep_kernel<FMT, MT, 1>, a, grid, S, lds, st);
+  if (kind == kSweep || kind == kSweepCached) {
+    if constexpr (FMT == FMT_FP16) {
+      if (lr == 1) return launch(sweep_kernel<FMT, MT, 1, false>, a, grid, S, lds, st);
+    } else {
+      if (lr == 2) return kind == kSweep ? launch(sweep_kernel<FMT, MT, 2, true>, a, grid, S, lds, st)
+                                         : launch(sweep_kernel<FMT, MT, 2, false>, a, grid, S, lds, st);
     }
   } else if (kind == kStream) {
     switch (lr) {
@@ -1085,9 +1123,11 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.spw = wp.spw;
     a.red_slots = 0;
     a.piece_q = a.piece_r = 0;
-    a.rc = n_rec;
-    return M <= 16 ? launch_by_ring<FMT, 1>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st)
-                   : launch_by_ring<FMT, 2>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st);
+    a.rc = wp.rc;
+    // measured: below about 24 MB of packed weights ordinary loads win, above that non-temporal ones
+    const KernelKind kind = n_strips * n_rec * (int64_t)Fmt<FMT>::REC_BYTES < (24ll << 20) ? kSweepCached : kSweep;
+    return M <= 16 ? launch_by_ring<FMT, 1>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st)
+                   : launch_by_ring<FMT, 2>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st);
   }
   const StreamPlan sp = make_stream_plan(FMT, M, n_strips, n_rec, REC_K);
   if (sp.ok) {

@@ -142,6 +142,31 @@ def test_linear_full_size_sampled_rows(fmt, ofmt):
     assert np.all(np.isfinite(y))
 
 
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize(
+    "N,K,Ms",
+    [
+        (28672, 4096, (1, 4, 16)),  # Llama-8B gate/up: 7 strips per workgroup; M=16 walks K in phases
+        (4200, 14336, (1, 8)),  # long K, workgroups with 2 strips and with 1; M=8 walks K in phases
+        (8200, 1000, (1, 32)),  # ragged everything, 3 strips per workgroup, two MFMA row tiles
+    ],
+)
+def test_linear_large_shapes_sampled_rows(fmt, ofmt, N, K, Ms):
+    # shapes whose workgroups own several strips, in the launch configuration the benchmark
+    # times; the oracle quantizes a sample of rows (rows are independent) and checks those outputs
+    W = synth.gaussian_weights(N, K, 81)
+    packed, scales = ams.ams_pack(fmt, W)
+    wp, sc = dev(packed), dev(scales)
+    rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(7, N, 131), 16 * 255 : 16 * 257 + 1])
+    rows = rows[rows < N]
+    codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+    for M in Ms:
+        X = synth.activations(M, K, 81 + M)
+        y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt)).astype(np.float64)
+        assert np.all(np.isfinite(y))
+        check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M} sample")
+
+
 @pytest.mark.parametrize("N,K,Ms", [(256, 768, (1, 2, 4, 8, 16, 32)), (37, 1000, (1, 7, 20)), (40, 14336, (1, 16))])
 def test_fp16_baseline_matches_oracle(N, K, Ms):
     W = synth.gaussian_weights(N, K, 71)

@@ -10,8 +10,9 @@ step rotates through several resident copies of each packed matrix (a real decod
 step touches each layer's weights once per token and the model never fits a cache).
 
 stdout carries ONE JSON line: whole-step packed-weight GB/s as `value`, per-layer
-figures (us per Linear, GB/s, fraction of the 8 TB/s HBM peak, speed-up over the
-in-build fp16 Linear) under `layers`, a `roofline` object for the dominant kernel
+figures (us per Linear with percentiles, cache-resident time, GB/s, fraction of the
+8 TB/s HBM peak and of a bare read of the same bytes, speed-up over the in-build fp16
+Linear and the library GEMM) under `layers`, a `roofline` object for the dominant kernel
 and a `cpu_baseline` object (the numpy oracle timed on this host).
 `--sweep` adds the batch sweep M = 1..32 (written to --out, default bench_sweep.json).
 """
@@ -74,10 +75,11 @@ class Layer:
         self.w16 = [w] + [w.clone() for _ in range(fp16_copies - 1)]
 
 
-def time_launches(torch, fn, n_launch, warm=2, replays=5):
+def time_launches(torch, fn, n_launch, warm=2, replays=5, spread=False):
     """Average GPU time per call of fn(i): n_launch back-to-back launches are captured in a HIP graph
     (so that the host's launch cost does not gate the measurement) and the graph is replayed between
-    two HIP events on the launch stream."""
+    HIP events on the launch stream.  spread=True times every replay by itself and also returns the
+    10th / 50th / 90th percentile of the per-replay averages."""
     g = torch.cuda.CUDAGraph()
     fn(0)
     torch.cuda.synchronize()
@@ -87,13 +89,19 @@ def time_launches(torch, fn, n_launch, warm=2, replays=5):
     for _ in range(warm):
         g.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(replays):
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+    ev[0].record()
+    for r in range(replays):
         g.replay()
-    e1.record()
+        if spread or r == replays - 1:
+            ev[r + 1].record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / (n_launch * replays)  # us
+    mean = ev[0].elapsed_time(ev[replays]) * 1e3 / (n_launch * replays)  # us
+    if not spread:
+        return mean
+    per = sorted(ev[r].elapsed_time(ev[r + 1]) * 1e3 / n_launch for r in range(replays))
+    pick = lambda q: per[min(len(per) - 1, int(q * len(per)))]
+    return mean, {"p10": round(pick(0.1), 3), "p50": round(pick(0.5), 3), "p90": round(pick(0.9), 3), "replays": replays, "launches_per_replay": n_launch}
 
 
 def cpu_baseline(seconds_hint=15.0):
@@ -241,13 +249,16 @@ def main():
         t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % fp16_copies], xs[l.name], out=ys[l.name]), n_launch)
         tlib = time_launches(torch, lambda i: torch.matmul(xs[l.name], l.w16[i % fp16_copies].t(), out=ys[l.name]), n_launch)
         for fmt in fmts:
-            t = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
+            t, pct = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch, replays=10, spread=True)
             warm = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
+            # second denominator: a bare read of the same packed bytes (same rotation), nothing computed
+            t_read = time_launches(torch, lambda i: ams.ams_read_probe(l.packed[fmt][i % n_copies]), n_launch)
             gbps = l.canon[fmt] / t / 1e3
             per_layer.append(
                 {
                     "layer": l.name, "N": l.N, "K": l.K, "M": M, "fmt": FMT_NAMES[fmt],
-                    "us": round(t, 3), "us_cache_resident": round(warm, 3),
+                    "us": round(t, 3), "us_percentiles": pct, "us_cache_resident": round(warm, 3),
+                    "bare_read_us": round(t_read, 3), "frac_of_bare_read": round(t_read / t, 4),
                     "packed_bytes": l.canon[fmt], "allocated_bytes": ams.ams_packed_bytes(fmt, l.N, l.K),
                     "GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
                     "fp16_us": round(t16, 3), "fp16_GBps": round(2 * l.N * l.K / t16 / 1e3, 1),
@@ -270,6 +281,9 @@ def main():
         "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes,
         "traffic": MEASURED_TRAFFIC_BYTES.get((dl.name, dom["fmt"], M)) if args.layers == "8b" else None,
     }
+
+    # launch floor: an empty launch of the Linear kernel's shape (256 workgroups x 1024 threads)
+    launch_floor = time_launches(torch, lambda i: ams.ams_read_probe(layers[0].packed[fmts[0]][0], 0), n_launch)
 
     sweep = None
     if args.sweep:
@@ -301,6 +315,7 @@ def main():
             if args.layers == "8b" else f"{args.layers} layer set, M=1, both formats",
             "linears_per_step": len(layers) * len(fmts), "packed_bytes_per_step": step_bytes,
             "hbm_peak_GBps": HBM_PEAK_GBPS, "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
+            "launch_floor_us": round(launch_floor, 3),
         },
         "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",

@@ -123,6 +123,17 @@ int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, 
  */
 int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* stream);
 
+/*
+ * Measurement aid, not part of the method: a bare streaming read of the first
+ * floor(bytes / 1024) KiB of `buf` (device, 16-byte aligned) in the order the Linear
+ * kernel sweeps a packed matrix, nothing computed, nothing stored.  Its time is the
+ * read ceiling of this GPU at that size, the second denominator (beside the 8 TB/s
+ * HBM peak) for the "saturate the memory subsystem" goal of Sec. 3.3; bytes < 1024
+ * gives an empty launch of the same shape (the launch floor).  `sink` is a device
+ * word the kernel may write (it practically never does) or NULL.
+ */
+int ams_read_probe(const void* buf, size_t bytes, uint32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -48,6 +48,7 @@ def load_library():
     lib.ams_dequant.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _int, _vp]
     lib.ams_linear.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp]
     lib.ams_fp16_linear.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp]
+    lib.ams_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
     _lib = lib
     return lib
 
@@ -169,3 +170,12 @@ def ams_fp16_linear(W, X, out=None):
     rc = load_library().ams_fp16_linear(_dev_ptr(W, torch.float16), _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K, _stream())
     _check(rc, "ams_fp16_linear")
     return out
+
+
+def ams_read_probe(buf, nbytes: int = None):
+    """Measurement aid: a bare streaming read of the first nbytes of a CUDA tensor (default: all of it)."""
+    if nbytes is None:
+        nbytes = buf.numel() * buf.element_size()
+    if nbytes > buf.numel() * buf.element_size():
+        raise ValueError("nbytes exceeds the buffer")
+    _check(load_library().ams_read_probe(_dev_ptr(buf), nbytes, None, _stream()), "ams_read_probe")

@@ -192,4 +192,15 @@ def test_device_entry_points_reject_bad_arguments():
     assert lib.ams_linear(p(wp) + 2, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -4
     assert lib.ams_dequant(3, p(wp), p(sc), p(y), 16, 96, 1, None) == -1
     assert lib.ams_fp16_linear(p(x), p(x), p(y), 1, 1, 95, None) == -2
+    assert lib.ams_read_probe(None, 1024, None, None) == -3
+    assert lib.ams_read_probe(p(wp) + 2, 1024, None, None) == -4
     torch.cuda.synchronize()
+
+
+def test_read_probe_runs_on_any_size_and_changes_nothing():
+    buf = torch.arange(3 * 1024 * 1024 + 700, dtype=torch.uint8, device="cuda")
+    before = buf.clone()
+    for nbytes in (0, 700, 1024, 17 * 1024, 1 << 20, buf.numel()):
+        ams.ams_read_probe(buf, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)

@@ -88,6 +88,20 @@ int ams_pack(int fmt, const uint16_t* W_fp16, int64_t N, int64_t K, int64_t ldw,
              uint16_t* scales_fp16, uint8_t* codes);
 
 /*
+ * ams_pack with a choice of the search (everything else as ams_pack):
+ *   AMS_SEARCH_SET_BIT  Sec. 3.1 as written: each member keeps the upper bits of its RTN
+ *                       code and only its last bit is set to the tried value.
+ *   AMS_SEARCH_REROUND  a variant that is not in the paper: for each tried value every
+ *                       member is re-rounded to the nearest code that ends in it (ties to
+ *                       the code whose upper part is even, saturating).  Never a larger
+ *                       error; the packed layout and the kernels are the same.
+ * Errors: as ams_pack; SHAPE for an unknown search.
+ */
+enum { AMS_SEARCH_SET_BIT = 0, AMS_SEARCH_REROUND = 1 };
+int ams_pack_ex(int fmt, int search, const uint16_t* W_fp16, int64_t N, int64_t K, int64_t ldw, void* packed,
+                uint16_t* scales_fp16, uint8_t* codes);
+
+/*
  * Pack codes that were produced elsewhere (e.g. read from the paper's layout) into
  * the gfx950 layout.  codes [N, K] as written by ams_pack; within a group all last
  * bits must agree (else AMS_ERR_SHAPE).  Host pointers.

@@ -178,7 +178,24 @@ def set_last_bit(codes: np.ndarray, m0: int) -> np.ndarray:
     return (np.asarray(codes) & ~1) | m0
 
 
-def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64):
+def reround_magnitude_codes(a: np.ndarray, fmt: Format, m0: int) -> np.ndarray:
+    """Nearest magnitude among the codes whose last mantissa bit is m0.
+
+    Not in the paper: the re-rounding variant of the search (see ams_quantize).
+    The argmin of Sec. 2.1 restricted to every other code.  An exact tie goes to
+    the code whose remaining bits (code >> 1) are even; inputs above the largest
+    such magnitude land on it.
+    """
+    a = np.asarray(a, dtype=np.float64)
+    table = magnitude_table(fmt)[m0::2]  # indexed by code >> 1
+    dist = np.abs(a[..., None] - table)
+    first = np.argmin(dist, axis=-1)
+    last = (len(table) - 1) - np.argmin(dist[..., ::-1], axis=-1)
+    upper = np.where(first % 2 == 0, first, last).astype(np.int64)
+    return 2 * upper + m0
+
+
+def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64, search: str = "set"):
     """Channel-wise RTN, grouping along K, adaptive search of the shared bit.
 
     Follows Sec. 3.1 in order: (1) RTN of every weight to FPx with one scale
@@ -194,9 +211,16 @@ def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64):
     * when K is not a multiple of the group size the last group is shorter:
       only its real members enter the sum (padding is never an output).
 
+    ``search="reround"`` is a variant that is NOT in the paper: for each value
+    of the shared bit every member is re-rounded to the nearest code that ends
+    in that bit (instead of keeping the upper bits of its RTN code); the rest
+    (squared errors, order, tie) is as above.  Its error can only be smaller.
+
     Returns (codes [N,K] int64 full codes whose LSB is the group's shared bit,
              scales [N] float16, shared [N, ceil(K/group)] uint8).
     """
+    if search not in ("set", "reround"):
+        raise ValueError(search)
     W = np.asarray(W)
     N, K = W.shape
     g = fmt.group
@@ -211,9 +235,15 @@ def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64):
         c_rtn = rtn_codes(Wc, sc, fmt)
         W64 = Wc.astype(np.float64)
         s64 = sc.astype(np.float64)[:, None]
-        sq = []
+        sq, cand = [], []
         for m0 in (0, 1):
-            deq = decode(set_last_bit(c_rtn, m0), fmt) * s64  # Eq. 2
+            if search == "set":
+                c_m0 = set_last_bit(c_rtn, m0)  # G(FPx_i, m0)
+            else:
+                sign = (W64 < 0).astype(np.int64) << (EXP_BITS + fmt.mbits)
+                c_m0 = sign | reround_magnitude_codes(np.abs(W64 / s64), fmt, m0)
+            cand.append(c_m0)
+            deq = decode(c_m0, fmt) * s64  # Eq. 2
             sq.append((deq - W64) ** 2)
         sse = [np.zeros((r1 - r0, n_groups)), np.zeros((r1 - r0, n_groups))]
         for j in range(g):  # member order; a short last group has fewer members
@@ -223,7 +253,7 @@ def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64):
         pick = (sse[1] < sse[0]).astype(np.int64)  # tie keeps 0
         shared[r0:r1] = pick
         per_weight = np.repeat(pick, g, axis=1)[:, :K]
-        codes[r0:r1] = (c_rtn & ~1) | per_weight
+        codes[r0:r1] = np.where(per_weight == 1, cand[1], cand[0])
     return codes, s, shared
 
 

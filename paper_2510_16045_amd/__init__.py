@@ -15,6 +15,8 @@ import numpy as np
 
 FP533 = 0  # AMS_FMT_FP533_E2M3
 FP425 = 1  # AMS_FMT_FP425_E2M2
+SEARCH_SET_BIT = 0  # AMS_SEARCH_SET_BIT
+SEARCH_REROUND = 1  # AMS_SEARCH_REROUND
 MAX_M = 32
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libams.so")
@@ -43,6 +45,7 @@ def load_library():
     lib.ams_packed_bytes.argtypes = [_int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.ams_canonical_bytes.argtypes = [_int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.ams_pack.argtypes = [_int, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
+    lib.ams_pack_ex.argtypes = [_int, _int, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
     lib.ams_pack_codes.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_unpack_host.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_dequant.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _int, _vp]
@@ -76,6 +79,20 @@ def ams_canonical_bytes(fmt: int, N: int, K: int) -> int:
     out = ctypes.c_size_t()
     _check(load_library().ams_canonical_bytes(fmt, N, K, ctypes.byref(out)), "ams_canonical_bytes")
     return out.value
+
+
+def ams_pack_ex(fmt: int, search: int, W: np.ndarray, return_codes: bool = False):
+    """Quantize + pack host fp16 weights [N,K] with the given search.  Returns (packed uint8, scales float16[, codes uint8])."""
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array")
+    W = np.ascontiguousarray(W)
+    N, K = W.shape
+    packed = np.empty(ams_packed_bytes(fmt, N, K), dtype=np.uint8)
+    scales = np.empty(N, dtype=np.float16)
+    codes = np.empty((N, K), dtype=np.uint8) if return_codes else None
+    rc = load_library().ams_pack_ex(fmt, search, _np_ptr(W), N, K, K, _np_ptr(packed), _np_ptr(scales), _np_ptr(codes) if return_codes else None)
+    _check(rc, "ams_pack_ex")
+    return (packed, scales, codes) if return_codes else (packed, scales)
 
 
 def ams_pack(fmt: int, W: np.ndarray, return_codes: bool = False):

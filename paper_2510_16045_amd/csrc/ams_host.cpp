@@ -71,9 +71,25 @@ inline int rtn_magnitude_code(double a, int mbits) {
   return std::min(code, 4 * one - 1);
 }
 
+// Re-rounding variant of the search (not in the paper): nearest magnitude among the codes
+// that end in m0.  The candidates are walked in order; an exact tie between two
+// neighbours goes to the one whose upper part (code >> 1) is even; inputs above the
+// largest candidate land on it.
+inline int reround_magnitude_code(double a, int mbits, int m0) {
+  const int n_upper = 2 << mbits;  // 4 * 2^mbits magnitude codes, every other one
+  int best = 0;
+  double best_d = std::fabs(a - magnitude(m0, mbits));
+  for (int j = 1; j < n_upper; j++) {
+    const double d = std::fabs(a - magnitude(2 * j + m0, mbits));
+    if (d < best_d || (d == best_d && (j & 1) == 0)) best = j, best_d = d;
+  }
+  return 2 * best + m0;
+}
+
 struct RowQuant {
   int mbits, group;
   double fmax;
+  int search;  // AMS_SEARCH_*
 };
 
 // Quantize one row: scale (Eq. 1), RTN, adaptive search of each group's shared bit.
@@ -91,20 +107,31 @@ bool quantize_row(const RowQuant& q, const uint16_t* w, int64_t K, uint8_t* code
   const int sign_shift = 2 + q.mbits;
   for (int64_t k0 = 0; k0 < K; k0 += q.group) {
     const int n = (int)std::min<int64_t>(q.group, K - k0);
-    int c[4];
+    int c[2][4];  // candidate codes of the members for shared bit 0 and 1
     double sse0 = 0, sse1 = 0;
     for (int i = 0; i < n; i++) {
       const double wv = half_to_double(w[k0 + i]);
-      const int mc = rtn_magnitude_code(std::fabs(wv / s), q.mbits);
-      c[i] = mc | ((wv < 0 ? 1 : 0) << sign_shift);
+      const double a = std::fabs(wv / s);
+      int mc0, mc1;
+      if (q.search == AMS_SEARCH_REROUND) {
+        mc0 = reround_magnitude_code(a, q.mbits, 0);
+        mc1 = reround_magnitude_code(a, q.mbits, 1);
+      } else {  // Sec. 3.1: the RTN code with its last bit set to m0
+        const int mc = rtn_magnitude_code(a, q.mbits);
+        mc0 = mc & ~1;
+        mc1 = mc | 1;
+      }
+      const int sign = (wv < 0 ? 1 : 0) << sign_shift;
+      c[0][i] = mc0 | sign;
+      c[1][i] = mc1 | sign;
       const double sg = wv < 0 ? -1.0 : 1.0;
-      const double d0 = sg * magnitude(mc & ~1, q.mbits) * s - wv;  // Eq. 2 with last bit 0
-      const double d1 = sg * magnitude(mc | 1, q.mbits) * s - wv;   // ... with last bit 1
+      const double d0 = sg * magnitude(mc0, q.mbits) * s - wv;  // Eq. 2 with last bit 0
+      const double d1 = sg * magnitude(mc1, q.mbits) * s - wv;  // ... with last bit 1
       sse0 = sse0 + d0 * d0;
       sse1 = sse1 + d1 * d1;
     }
     const int m0 = sse1 < sse0 ? 1 : 0;  // a tie keeps 0
-    for (int i = 0; i < n; i++) codes[k0 + i] = (uint8_t)((c[i] & ~1) | m0);
+    for (int i = 0; i < n; i++) codes[k0 + i] = (uint8_t)c[m0][i];
   }
   return true;
 }
@@ -262,11 +289,17 @@ int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
 
 int ams_pack(int fmt, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed, uint16_t* scales,
              uint8_t* codes_out) {
+  return ams_pack_ex(fmt, AMS_SEARCH_SET_BIT, W, N, K, ldw, packed, scales, codes_out);
+}
+
+int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed, uint16_t* scales,
+                uint8_t* codes_out) {
   if (int rc = check_shape(fmt, N, K)) return rc;
+  if (search != AMS_SEARCH_SET_BIT && search != AMS_SEARCH_REROUND) return AMS_ERR_SHAPE;
   if (!W || !packed || !scales) return AMS_ERR_NULL;
   if (ldw < K) return AMS_ERR_SHAPE;
   const FormatInfo& fi = *ams::format_info(fmt);
-  const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax};
+  const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax, search};
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
   const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   std::atomic<int> bad{0};

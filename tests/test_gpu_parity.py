@@ -96,6 +96,20 @@ def test_linear_matches_oracle(fmt, ofmt, N, K, Ms):
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_reround_packed_weights_through_the_kernels(fmt, ofmt):
+    # the re-rounding search only changes which codes are packed: same layout, same kernels
+    N, K = 100, 1030
+    W = synth.gaussian_weights(N, K, 45)
+    packed, scales = ams.ams_pack_ex(fmt, ams.SEARCH_REROUND, W)
+    codes, o_scales, _ = O.ams_quantize(W, ofmt, search="reround")
+    got = host16(ams.ams_dequant(fmt, dev(packed), dev(scales), N, K, scaled=True))
+    assert np.array_equal(got.view(np.uint16), O.dequant_scaled(codes, o_scales, ofmt).view(np.uint16))
+    X = synth.activations(3, K, 46)
+    y = host16(ams.ams_linear(dev(packed), dev(scales), dev(X), N, fmt))
+    check_linear(y, O.linear(codes, o_scales, X, ofmt), "reround")
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_linear_heavy_tail_weights_and_outlier_activations(fmt, ofmt):
     N, K = 64, 8192
     W = synth.heavy_tail_weights(N, K, 51)

@@ -79,6 +79,37 @@ def test_quantizer_on_every_fp16_value(fmt, ofmt):
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("maker,N,K", [(synth.gaussian_weights, 64, 770), (synth.heavy_tail_weights, 33, 2050), (synth.gaussian_weights, 2, 4)])
+def test_reround_search_matches_oracle_bit_for_bit(fmt, ofmt, maker, N, K):
+    W = maker(N, K, 23)
+    packed, scales, codes = ams.ams_pack_ex(fmt, ams.SEARCH_REROUND, W, return_codes=True)
+    o_codes, o_scales, _ = O.ams_quantize(W, ofmt, search="reround")
+    assert np.array_equal(scales.view(np.uint16), o_scales.view(np.uint16))
+    assert np.array_equal(codes, o_codes.astype(np.uint8))
+    assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
+    # the literal search through the same entry point is ams_pack
+    p2, s2, c2 = ams.ams_pack_ex(fmt, ams.SEARCH_SET_BIT, W, return_codes=True)
+    p1, s1, c1 = ams.ams_pack(fmt, W, return_codes=True)
+    assert np.array_equal(p1, p2) and np.array_equal(s1, s2) and np.array_equal(c1, c2)
+    with pytest.raises(ams.AmsError):
+        ams.ams_pack_ex(fmt, 7, W)
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_reround_search_on_every_fp16_value(fmt, ofmt):
+    v = np.arange(1 << 16, dtype=np.uint16).view(np.float16)
+    v = v[np.isfinite(v)]
+    for top in (7.5, 1.0, 0.0137):
+        row = v[np.abs(v.astype(np.float64)) <= top]
+        W = row[: (len(row) // 12) * 12].reshape(1, -1).copy()
+        W[0, 0] = np.float16(top)
+        _, scales, codes = ams.ams_pack_ex(fmt, ams.SEARCH_REROUND, W, return_codes=True)
+        o_codes, o_scales, _ = O.ams_quantize(W, ofmt, search="reround")
+        assert np.array_equal(scales, o_scales)
+        assert np.array_equal(codes, o_codes.astype(np.uint8))
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_degenerate_rows_and_errors(fmt, ofmt):
     W = np.zeros((3, 24), dtype=np.float16)
     W[1, 5] = np.float16(6e-8)

@@ -209,6 +209,87 @@ def test_search_is_globally_optimal_on_tiny_matrices(fmt):
         assert abs(mine - best[0]) <= 1e-12 * best[0]
 
 
+# ---- the re-rounding variant of the search (not in the paper) ---------------------------------
+@pytest.mark.parametrize("big,small", [(O.FP6_E2M3, O.FP5_E2M2), (O.FP5_E2M2, O.FP4_E2M1)])
+def test_reround_to_bit_zero_is_rtn_of_the_format_with_one_bit_less(big, small):
+    # the codes ending in 0 are the value set of the format with one mantissa bit less
+    # (test_value_sets_closed_form), so re-rounding to them is that format's plain RTN
+    a = np.abs(np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64))
+    for scale in (1.0, 0.37, 3.0):
+        assert np.array_equal(O.reround_magnitude_codes(a / scale, big, 0) >> 1, O.rtn_magnitude_codes(a / scale, small))
+
+
+@pytest.mark.parametrize("fmt", [O.FP6_E2M3, O.FP5_E2M2])
+def test_reround_to_bit_one_is_nearest_and_ties_follow_the_rule(fmt):
+    odd = O.magnitude_table(fmt)[1::2]
+    a = np.abs(np.arange(0, 0x4900, dtype=np.uint16).view(np.float16).astype(np.float64))  # 0 .. 10
+    got = O.reround_magnitude_codes(a, fmt, 1)
+    assert np.all(got & 1 == 1)
+    for x, c in zip(a.tolist(), got.tolist()):  # scalar brute force, the definition
+        d = [abs(x - v) for v in odd.tolist()]
+        assert d[c >> 1] == min(d)
+    mids = (odd[:-1] + odd[1:]) / 2  # exact ties: the even one of the two upper parts wins
+    tie = O.reround_magnitude_codes(mids, fmt, 1) >> 1
+    assert np.all(tie % 2 == 0) and np.all((tie == np.arange(len(mids))) | (tie == np.arange(len(mids)) + 1))
+    assert O.reround_magnitude_codes(np.array([1e9]), fmt, 1)[0] == fmt.n_mag - 1  # saturates
+
+
+@pytest.mark.parametrize("fmt", AMS + [O.FP45, O.FP433])
+def test_reround_search_invariants(fmt):
+    K = 100
+    W = synth.gaussian_weights(32, K, 77)
+    c_set, s, _ = O.ams_quantize(W, fmt)
+    c_rr, s_rr, shared = O.ams_quantize(W, fmt, search="reround")
+    assert np.array_equal(s, s_rr)
+    g = fmt.group
+    assert np.array_equal(c_rr & 1, np.repeat(shared, g, axis=1)[:, :K])
+    sign_bit = fmt.code_bits - 1
+    assert np.array_equal(c_rr >> sign_bit, (W < 0).astype(np.int64))
+    W64 = W.astype(np.float64)
+    one_less = O.Format("one-less", fmt.mbits - 1, 1)
+    t = np.abs(W64 / s.astype(np.float64)[:, None])
+    c_low = ((W < 0).astype(np.int64) << sign_bit) | (O.rtn_magnitude_codes(t, one_less) << 1)
+    err = lambda c: (O.decode(c, fmt) * s.astype(np.float64)[:, None] - W64) ** 2
+    e_rr, e_set, e_low = err(c_rr), err(c_set), err(c_low)
+    strictly = 0
+    for gi in range(-(-K // g)):
+        sl = slice(gi * g, min(K, gi * g + g))
+        a, b, c = e_rr[:, sl].sum(1), e_set[:, sl].sum(1), e_low[:, sl].sum(1)
+        assert np.all(a <= b * (1 + 1e-12) + 1e-30)  # never worse than setting the bit
+        assert np.all(a <= c * (1 + 1e-12) + 1e-30)  # never worse than plain RTN with one bit less
+        strictly += int(np.sum(a < b * (1 - 1e-9)))
+    assert strictly > 0  # and it does help somewhere
+
+
+@pytest.mark.parametrize("fmt", AMS)
+def test_reround_search_is_optimal_over_all_codes_with_a_common_last_bit(fmt):
+    # brute force: every tuple of codes of a group that ends in the same bit (scalar arithmetic)
+    W = synth.gaussian_weights(3, 2 * fmt.group + 1, 9)
+    codes, s, _ = O.ams_quantize(W, fmt, search="reround")
+    g, K = fmt.group, W.shape[1]
+    mags = [O.magnitude_of(c, fmt.mbits) for c in range(fmt.n_mag)]
+    for n in range(W.shape[0]):
+        sc = float(s[n])
+        for k0 in range(0, K, g):
+            ws = [float(W[n, k]) for k in range(k0, min(K, k0 + g))]
+            best = None
+            for m0 in (0, 1):
+                cand = [c for c in range(fmt.n_mag) if c & 1 == m0]
+                for tup in itertools.product(cand, repeat=len(ws)):
+                    # the sign is fixed by the weight, so only magnitudes are enumerated
+                    tot = 0.0
+                    for w, c in zip(ws, tup):
+                        v = -mags[c] if w < 0 else mags[c]
+                        tot += (v * sc - w) ** 2
+                    if best is None or tot < best:
+                        best = tot
+            mine = 0.0
+            for w, c in zip(ws, codes[n, k0 : k0 + g].tolist()):
+                v = mags[c & (fmt.n_mag - 1)]
+                mine += ((-v if w < 0 else v) * sc - w) ** 2
+            assert abs(mine - best) <= 1e-12 * max(best, 1e-300)
+
+
 def test_worked_groups_fixture():
     names = {"fp4.25": O.FP425, "fp5.33": O.FP533}
     n = 0

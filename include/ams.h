@@ -28,10 +28,18 @@
 extern "C" {
 #endif
 
-/* Formats (abstract; Sec. 3.2, Sec. 3.3 item 1). */
+/*
+ * Formats.  The two the paper builds kernels for (abstract; Sec. 3.2, Sec. 3.3 item 1),
+ * the other shared-bit formats it evaluates (Sec. 4.1, FP(x-1).y with y = 1/k), and the
+ * plain mini-floats it compares with (group size 1: no sharing, the search is a no-op).
+ */
 enum {
   AMS_FMT_FP533_E2M3 = 0, /* e2m3 codes, groups of 3 along K share the mantissa LSB: 16/3 bits per weight */
-  AMS_FMT_FP425_E2M2 = 1  /* e2m2 codes, groups of 4 along K share the mantissa LSB: 4.25 bits per weight */
+  AMS_FMT_FP425_E2M2 = 1, /* e2m2 codes, groups of 4 share it: 4.25 bits per weight */
+  AMS_FMT_FP45_E2M2 = 2,  /* e2m2 codes, groups of 2 share it: 4.5 bits per weight */
+  AMS_FMT_FP433_E2M2 = 3, /* e2m2 codes, groups of 3 share it: 13/3 bits per weight */
+  AMS_FMT_FP6_E2M3 = 4,   /* plain e2m3: 6 bits per weight */
+  AMS_FMT_FP5_E2M2 = 5    /* plain e2m2: 5 bits per weight */
 };
 
 enum {
@@ -57,16 +65,19 @@ int ams_code_bits(int fmt);
 /*
  * Size in bytes of the packed weight buffer in this library's gfx950 layout
  * (what ams_pack writes and ams_dequant / ams_linear read).  The layout is opaque:
- * 16-row x 96-weight (FP5.33) or 16-row x 128-weight (FP4.25) records of 64
- * 16-byte lane chunks, so N is padded to a multiple of 16 and K to a multiple of
- * 96 / 128; padding holds zero codes.
+ * records of 16 rows x 96 weights (FP5.33, FP4.33, FP6) or 16 rows x 128 weights
+ * (FP4.25, FP4.5, FP5), so N is padded to a multiple of 16 and K to a multiple of
+ * 96 / 128; padding holds zero codes.  Without padding the size is exactly
+ * N * K * bits-per-weight / 8.
  */
 int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
 
 /*
  * Size in bytes of the paper's own packing: one uint16 per 3 weights for FP5.33
- * (Sec. 3.3 item 1), 17 uint16 per 64 weights for FP4.25 (Sec. 3.2).  This is the
- * "algorithmic" byte count used when bandwidth is reported.
+ * (Sec. 3.3 item 1), 17 uint16 per 64 weights for FP4.25 (Sec. 3.2); for the other
+ * formats the densest whole-byte packing per row (9 bytes per 16 weights, 13 per 24,
+ * 3 per 4, 5 per 8).  This is the "algorithmic" byte count used when bandwidth is
+ * reported.
  */
 int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
 

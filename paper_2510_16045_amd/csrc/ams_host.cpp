@@ -137,80 +137,68 @@ bool quantize_row(const RowQuant& q, const uint16_t* w, int64_t K, uint8_t* code
 }
 
 // ---- layout ---------------------------------------------------------------
+inline bool is_e2m3(int fmt) { return fmt == ams::kFmtFp533 || fmt == ams::kFmtFp6; }
+
+// Bit positions of member i's sign and magnitude inside a half-word, and the bit
+// (or -1) of the half-word that holds a last mantissa bit.
+inline int sign_pos(int fmt, int i) {
+  if (is_e2m3(fmt)) return 15 - i;
+  constexpr int pos[4] = {15, 12, 14, 13};
+  return pos[i];
+}
+inline int mag_pos(int fmt, int i) { return is_e2m3(fmt) ? 8 - 4 * i : 9 - 3 * i; }
+
 // Writes the records of one strip.  codes: 16 rows of K bytes (row pointer NULL = padding row).
 void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], int64_t K, uint8_t* strip_out) {
   const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
+  const int mag_bits = fi.code_bits - 2;  // bits of a remainder without its sign
   for (int64_t j = 0; j < n_rec; j++) {
     uint8_t* rec = strip_out + j * fi.rec_bytes;
     for (int l = 0; l < ams::kLanes; l++) {
       const uint8_t* row = rows[l & 15];
       const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
-      auto code_at = [&](int i) -> int { return (row && kbase + i < K) ? row[kbase + i] : 0; };
-      uint32_t words[4];
-      uint32_t shared_byte = 0;
-      for (int d = 0; d < 4; d++) {
-        uint32_t half[2];
-        for (int h = 0; h < 2; h++) {
-          if (fmt == AMS_FMT_FP425_E2M2) {
-            int rem[4], sh = 0;
-            for (int i = 0; i < 4; i++) {
-              int c = code_at(8 * d + 4 * h + i);
-              rem[i] = c >> 1;
-              sh |= c & 1;  // members agree (checked by the caller); padding is 0
-            }
-            auto sg = [&](int i) { return (uint32_t)(rem[i] >> 3); };
-            auto mg = [&](int i) { return (uint32_t)(rem[i] & 7); };
-            half[h] = sg(0) << 15 | sg(2) << 14 | sg(3) << 13 | sg(1) << 12 | mg(0) << 9 | mg(1) << 6 | mg(2) << 3 | mg(3);
-            shared_byte |= (uint32_t)sh << (4 * h + d);
-          } else {
-            int rem[3], sh = 0;
-            for (int i = 0; i < 3; i++) {
-              int c = code_at(6 * d + 3 * h + i);
-              rem[i] = c >> 1;
-              sh |= c & 1;
-            }
-            auto sg = [&](int i) { return (uint32_t)(rem[i] >> 4); };
-            auto mg = [&](int i) { return (uint32_t)(rem[i] & 15); };
-            half[h] = sg(0) << 15 | sg(1) << 14 | sg(2) << 13 | (uint32_t)sh << 12 | mg(0) << 8 | mg(1) << 4 | mg(2);
-          }
-        }
-        words[d] = half[0] | half[1] << 16;
+      uint32_t words[4] = {0, 0, 0, 0};
+      uint32_t side = 0;
+      for (int q = 0; q < fi.lane_k; q++) {
+        const int c = (row && kbase + q < K) ? row[kbase + q] : 0;  // padding is code 0
+        const ams::Place p = ams::place(fmt, q);
+        const uint32_t rem = (uint32_t)c >> 1, lsb = (uint32_t)c & 1;
+        uint32_t hw = (rem >> mag_bits) << sign_pos(fmt, p.i) | (rem & ((1u << mag_bits) - 1)) << mag_pos(fmt, p.i);
+        const int sb = ams::side_bit(fmt, q);
+        if (sb >= 0)
+          side |= lsb << sb;  // members of a group agree (checked by the caller)
+        else
+          hw |= lsb << 12;
+        words[p.d] |= hw << (16 * p.h);
       }
-      std::memcpy(rec + l * ams::kLaneChunkBytes, words, 16);
-      if (fmt == AMS_FMT_FP425_E2M2) rec[1024 + l] = (uint8_t)shared_byte;
+      std::memcpy(rec + l * fi.chunk_bytes, words, (size_t)fi.chunk_bytes);
+      for (int b = 0; b < fi.side_bytes; b++) rec[ams::kLanes * fi.chunk_bytes + l * fi.side_bytes + b] = (uint8_t)(side >> (8 * b));
     }
   }
 }
 
 void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* strip_in, int64_t K, uint8_t* const rows[16]) {
   const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
+  const int mag_bits = fi.code_bits - 2;
   for (int64_t j = 0; j < n_rec; j++) {
     const uint8_t* rec = strip_in + j * fi.rec_bytes;
     for (int l = 0; l < ams::kLanes; l++) {
       uint8_t* row = rows[l & 15];
       if (!row) continue;
       const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
-      uint32_t words[4];
-      std::memcpy(words, rec + l * ams::kLaneChunkBytes, 16);
-      const uint32_t shared_byte = fmt == AMS_FMT_FP425_E2M2 ? rec[1024 + l] : 0;
-      for (int d = 0; d < 4; d++)
-        for (int h = 0; h < 2; h++) {
-          const uint32_t hw = (words[d] >> (16 * h)) & 0xFFFF;
-          if (fmt == AMS_FMT_FP425_E2M2) {
-            const uint32_t sh = (shared_byte >> (4 * h + d)) & 1;
-            const uint32_t sg[4] = {hw >> 15 & 1, hw >> 12 & 1, hw >> 14 & 1, hw >> 13 & 1};
-            for (int i = 0; i < 4; i++) {
-              const int64_t k = kbase + 8 * d + 4 * h + i;
-              if (k < K) row[k] = (uint8_t)(((sg[i] << 3 | ((hw >> (9 - 3 * i)) & 7)) << 1) | sh);
-            }
-          } else {
-            const uint32_t sh = hw >> 12 & 1;
-            for (int i = 0; i < 3; i++) {
-              const int64_t k = kbase + 6 * d + 3 * h + i;
-              if (k < K) row[k] = (uint8_t)((((hw >> (15 - i)) & 1) << 4 | ((hw >> (8 - 4 * i)) & 15)) << 1 | sh);
-            }
-          }
-        }
+      uint32_t words[4] = {0, 0, 0, 0};
+      std::memcpy(words, rec + l * fi.chunk_bytes, (size_t)fi.chunk_bytes);
+      uint32_t side = 0;
+      for (int b = 0; b < fi.side_bytes; b++) side |= (uint32_t)rec[ams::kLanes * fi.chunk_bytes + l * fi.side_bytes + b] << (8 * b);
+      for (int q = 0; q < fi.lane_k; q++) {
+        if (kbase + q >= K) continue;
+        const ams::Place p = ams::place(fmt, q);
+        const uint32_t hw = (words[p.d] >> (16 * p.h)) & 0xFFFF;
+        const uint32_t rem = ((hw >> sign_pos(fmt, p.i)) & 1) << mag_bits | ((hw >> mag_pos(fmt, p.i)) & ((1u << mag_bits) - 1));
+        const int sb = ams::side_bit(fmt, q);
+        const uint32_t lsb = sb >= 0 ? (side >> sb) & 1 : (hw >> 12) & 1;
+        row[kbase + q] = (uint8_t)(rem << 1 | lsb);
+      }
     }
   }
 }
@@ -280,10 +268,14 @@ int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
 int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
   if (int rc = check_shape(fmt, N, K)) return rc;
   if (!bytes) return AMS_ERR_NULL;
-  if (fmt == AMS_FMT_FP533_E2M3)
-    *bytes = (size_t)2 * (size_t)((K + 2) / 3) * (size_t)N;  // one uint16 per 3 weights
-  else
-    *bytes = (size_t)34 * (size_t)((K + 63) / 64) * (size_t)N;  // 17 uint16 per 64 weights
+  switch (fmt) {
+    case AMS_FMT_FP533_E2M3: *bytes = (size_t)2 * (size_t)((K + 2) / 3) * (size_t)N; break;     // one uint16 per 3 weights
+    case AMS_FMT_FP425_E2M2: *bytes = (size_t)34 * (size_t)((K + 63) / 64) * (size_t)N; break;  // 17 uint16 per 64 weights
+    case AMS_FMT_FP45_E2M2: *bytes = (size_t)9 * (size_t)((K + 15) / 16) * (size_t)N; break;    // 16 nibbles + 8 shared bits
+    case AMS_FMT_FP433_E2M2: *bytes = (size_t)13 * (size_t)((K + 23) / 24) * (size_t)N; break;  // 24 nibbles + 8 shared bits
+    case AMS_FMT_FP6_E2M3: *bytes = (size_t)3 * (size_t)((K + 3) / 4) * (size_t)N; break;       // 4 codes of 6 bits
+    default: *bytes = (size_t)5 * (size_t)((K + 7) / 8) * (size_t)N; break;                     // FP5: 8 codes of 5 bits
+  }
   return AMS_OK;
 }
 

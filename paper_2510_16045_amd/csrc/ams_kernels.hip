@@ -31,7 +31,13 @@ typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
 constexpr int FMT_FP533 = AMS_FMT_FP533_E2M3;
 constexpr int FMT_FP425 = AMS_FMT_FP425_E2M2;
-constexpr int FMT_FP16 = 2;  // internal: unquantized row-major fp16 weights (baseline)
+constexpr int FMT_FP45 = AMS_FMT_FP45_E2M2;
+constexpr int FMT_FP433 = AMS_FMT_FP433_E2M2;
+constexpr int FMT_FP6 = AMS_FMT_FP6_E2M3;
+constexpr int FMT_FP5 = AMS_FMT_FP5_E2M2;
+constexpr int FMT_FP16 = 100;  // internal: unquantized row-major fp16 weights (baseline)
+static_assert(FMT_FP533 == ams::kFmtFp533 && FMT_FP425 == ams::kFmtFp425 && FMT_FP45 == ams::kFmtFp45 &&
+              FMT_FP433 == ams::kFmtFp433 && FMT_FP6 == ams::kFmtFp6 && FMT_FP5 == ams::kFmtFp5, "format numbers");
 
 constexpr float kTwo14 = 16384.0f;  // restored patterns are value * 2^-14
 
@@ -42,61 +48,88 @@ __device__ __forceinline__ uint32_t pk_mul_u16(uint32_t a, uint32_t c) {
   return __builtin_bit_cast(uint32_t, (us2)(x * y));
 }
 
-// FP4.25 (Sec. 3.2): one 32-bit word = two groups of four 4-bit remainders, plus their
-// two shared bits already placed at bits 8 and 24 of `sh`.  Produces the four fp16
-// pairs (A_i low, B_i high) as bit patterns of value * 2^-14:
-// sign -> bit 15, e1 e0 m1 -> bits 11..9, shared m0 -> bit 8.
-__device__ __forceinline__ void restore_fp425(uint32_t s, uint32_t sh, uint32_t out[4]) {
+// e2m2 formats (Sec. 3.2): one 32-bit word = two half-words of four 4-bit remainders.
+// sh[t] holds the last mantissa bits of pair t already placed at bits 8 and 24.
+// Produces the four fp16 pairs (A_t low, B_t high) as bit patterns of value * 2^-14:
+// sign -> bit 15, e1 e0 m1 -> bits 11..9, last bit m0 -> bit 8.
+__device__ __forceinline__ void restore_e2m2(uint32_t s, const uint32_t sh[4], uint32_t out[4]) {
   constexpr uint32_t M = 0x8E008E00u;
-  out[0] = bfi(M, s, sh);
-  out[1] = bfi(M, s << 3, sh);
+  out[0] = bfi(M, s, sh[0]);
+  out[1] = bfi(M, s << 3, sh[1]);
   // members 2 and 3: sign and magnitude need different shifts; a packed 16-bit
   // multiply by (2^a + 2^b) makes both shifted copies at once
-  out[2] = bfi(M, pk_mul_u16(s & 0x40384038u, 0x00420042u), sh);
-  out[3] = bfi(M, pk_mul_u16(s & 0x20072007u, 0x02040204u), sh);
+  out[2] = bfi(M, pk_mul_u16(s & 0x40384038u, 0x00420042u), sh[2]);
+  out[3] = bfi(M, pk_mul_u16(s & 0x20072007u, 0x02040204u), sh[3]);
+}
+// FP4.25: the four members of a half-word are one group, one pair of shared bits per word
+__device__ __forceinline__ void restore_fp425(uint32_t s, uint32_t sh, uint32_t out[4]) {
+  const uint32_t same[4] = {sh, sh, sh, sh};
+  restore_e2m2(s, same, out);
 }
 
-// Shared bits of a lane's FP4.25 record byte: bit d = group A of word d, bit 4+d = group B.
-__device__ __forceinline__ uint32_t spread_shared_fp425(uint32_t byte) { return byte | (byte << 12); }
-__device__ __forceinline__ uint32_t shared_of_word_fp425(uint32_t spread, int d) {
-  return (spread << (8 - d)) & 0x01000100u;
-}
+// Last bits kept in a side byte: bit t belongs to pair t's A half, bit 4+t to its B half.
+__device__ __forceinline__ uint32_t spread_side_byte(uint32_t byte) { return byte | (byte << 12); }
+__device__ __forceinline__ uint32_t pair_bits_e2m2(uint32_t spread, int t) { return (spread << (8 - t)) & 0x01000100u; }
 
-// FP5.33 (Sec. 3.3 item 1): one 32-bit word = two half-words, each a whole group (three
-// 5-bit remainders + the shared bit).  Produces three fp16 pairs (A_i low, B_i high):
-// sign -> bit 15, e1 e0 m2 m1 -> bits 11..8, shared m0 -> bit 7.
-__device__ __forceinline__ void restore_fp533(uint32_t s, uint32_t out[3]) {
+// e2m3 formats (Sec. 3.3 item 1): one 32-bit word = two half-words of three 5-bit
+// remainders; sh0..sh2 hold the last bits of the three pairs at bits 7 and 23.
+// Produces three fp16 pairs (A_i low, B_i high): sign -> bit 15, e1 e0 m2 m1 ->
+// bits 11..8, last bit m0 -> bit 7.
+__device__ __forceinline__ void restore_e2m3(uint32_t s, uint32_t sh0, uint32_t sh1, uint32_t sh2, uint32_t out[3]) {
   constexpr uint32_t M = 0x8F008F00u;
+  out[0] = bfi(M, s, sh0);
+  out[1] = bfi(0x80008000u, s << 1, ((s << 4) & 0x0F000F00u) | sh1);
+  out[2] = bfi(M, pk_mul_u16(s & 0x200F200Fu, 0x01040104u), sh2);
+}
+// FP5.33: each half-word is a whole group, its shared bit sits at bit 12
+__device__ __forceinline__ void restore_fp533(uint32_t s, uint32_t out[3]) {
   const uint32_t sh = (s >> 5) & 0x00800080u;
-  out[0] = bfi(M, s, sh);
-  out[1] = bfi(0x80008000u, s << 1, ((s << 4) & 0x0F000F00u) | sh);
-  out[2] = bfi(M, pk_mul_u16(s & 0x200F200Fu, 0x01040104u), sh);
+  restore_e2m3(s, sh, sh, sh, out);
 }
 
 template <int FMT>
-struct Fmt;
-template <>
-struct Fmt<FMT_FP533> {
-  static constexpr int REC_K = 96, REC_BYTES = 1024, N_MFMA = 3;
-};
-template <>
-struct Fmt<FMT_FP425> {
-  static constexpr int REC_K = 128, REC_BYTES = 1088, N_MFMA = 4;
+struct Fmt {
+  static constexpr int REC_K = ams::kFormats[FMT].rec_k, REC_BYTES = ams::kFormats[FMT].rec_bytes,
+                       CHUNK = ams::kFormats[FMT].chunk_bytes, SIDE = ams::kFormats[FMT].side_bytes,
+                       PB = ams::kFormats[FMT].perm_block, N_MFMA = REC_K / 32;
 };
 template <>
 struct Fmt<FMT_FP16> {
-  static constexpr int REC_K = 128, REC_BYTES = 0, N_MFMA = 4;
+  static constexpr int REC_K = 128, REC_BYTES = 0, CHUNK = 0, SIDE = 0, PB = 8, N_MFMA = 4;
 };
 
-// What one lane holds of one record.
+// Input channel (inside its permutation block) of every operand slot of the block.
 template <int FMT>
-struct LaneRec {
-  u4 w;
+struct SlotChannel {
+  int v[Fmt<FMT>::PB];
+  constexpr SlotChannel() : v{} {
+    for (int i = 0; i < Fmt<FMT>::PB; i++) v[i] = FMT == FMT_FP16 ? i : ams::slot_channel(FMT == FMT_FP16 ? 0 : FMT, i);
+  }
+};
+template <int FMT>
+__device__ constexpr int slot_channel(int s) {
+  constexpr SlotChannel<FMT> tab{};
+  return tab.v[s];
+}
+
+// What one lane holds of one record: the words of its chunk and its side bytes.
+template <int SIDE>
+struct SideBits {
+  uint32_t t;
 };
 template <>
-struct LaneRec<FMT_FP425> {
-  u4 w;
-  uint8_t t;  // kept as a byte: it is widened where it is used, behind that record's own wait
+struct SideBits<0> {};
+template <>
+struct SideBits<1> {
+  uint8_t t;  // kept narrow: it is widened where it is used, behind that record's own wait
+};
+template <>
+struct SideBits<2> {
+  uint16_t t;
+};
+template <int FMT>
+struct LaneRec : SideBits<Fmt<FMT>::SIDE> {
+  uint32_t w[Fmt<FMT>::CHUNK / 4];
 };
 template <>
 struct LaneRec<FMT_FP16> {
@@ -121,6 +154,62 @@ struct LinearArgs {
   int rc;                // stream kernel: records per strip in one phase of K
 };
 
+// One lane's part of the record at `base`: its chunk (one dwordx4, or three dwords that the
+// compiler merges) and its side bytes.
+template <int FMT, bool NT>
+__device__ __forceinline__ void load_lane_rec(LaneRec<FMT>& r, const uint8_t* base, int lane) {
+  constexpr int CHUNK = Fmt<FMT>::CHUNK, SIDE = Fmt<FMT>::SIDE;
+  auto ld = [](auto* p) { return NT ? __builtin_nontemporal_load(p) : *p; };
+  if constexpr (CHUNK == 16) {
+    const u4 v = ld((const u4*)(base + lane * 16));
+    r.w[0] = v[0], r.w[1] = v[1], r.w[2] = v[2], r.w[3] = v[3];
+  } else {
+    const uint32_t* p = (const uint32_t*)(base + lane * CHUNK);
+#pragma unroll
+    for (int d = 0; d < CHUNK / 4; d++) r.w[d] = ld(p + d);
+  }
+  const uint8_t* side = base + 64 * CHUNK + lane * SIDE;
+  if constexpr (SIDE == 1) r.t = ld(side);
+  if constexpr (SIDE == 2) r.t = ld((const uint16_t*)side);
+  if constexpr (SIDE == 4) r.t = ld((const uint32_t*)side);
+}
+
+// The MFMA A operands of one record as packed fp16 pairs: o[4u + t] = elements 2t, 2t+1
+// of the lane's row in MFMA u (bit patterns of value * 2^-14).
+template <int FMT>
+__device__ __forceinline__ void restore_rec(const LaneRec<FMT>& r, uint32_t (&o)[4 * Fmt<FMT>::N_MFMA]) {
+  if constexpr (FMT == FMT_FP533) {
+#pragma unroll
+    for (int d = 0; d < 4; d++) restore_fp533(r.w[d], &o[3 * d]);
+  } else if constexpr (FMT == FMT_FP6) {
+    // side bits: bit 2d + (i-1) = member i of half A of word d, the same + 8 for half B
+    const uint32_t t = r.t;
+    const uint32_t spread = (t & 0xFFu) | ((t & 0xFF00u) << 8);
+#pragma unroll
+    for (int d = 0; d < 4; d++)
+      restore_e2m3(r.w[d], (r.w[d] >> 5) & 0x00800080u, (spread << (7 - 2 * d)) & 0x00800080u, (spread << (6 - 2 * d)) & 0x00800080u,
+                   &o[3 * d]);
+  } else if constexpr (FMT == FMT_FP425) {
+    const uint32_t spread = spread_side_byte((uint32_t)r.t);
+#pragma unroll
+    for (int d = 0; d < 4; d++) restore_fp425(r.w[d], pair_bits_e2m2(spread, d), &o[4 * d]);
+  } else {
+    // FP4.33: one side byte for all words; FP4.5: one per two words; FP5: one per word
+    constexpr int WORDS_PER_BYTE = FMT == FMT_FP433 ? 3 : (FMT == FMT_FP45 ? 2 : 1);
+    const uint32_t t = r.t;
+    uint32_t sh[4];
+#pragma unroll
+    for (int d = 0; d < Fmt<FMT>::CHUNK / 4; d++) {
+      if (d % WORDS_PER_BYTE == 0) {
+        const uint32_t spread = spread_side_byte(Fmt<FMT>::SIDE == 1 ? t : (t >> (8 * (d / WORDS_PER_BYTE))) & 0xFFu);
+#pragma unroll
+        for (int i = 0; i < 4; i++) sh[i] = pair_bits_e2m2(spread, i);
+      }
+      restore_e2m2(r.w[d], sh, &o[4 * d]);
+    }
+  }
+}
+
 // Unconditional loads of one record (rec must be a valid record of the strip).  NT: packed
 // records bypass the caches' retention (they are read once); matrices small enough to
 // sit in the last-level cache between calls are better served by ordinary loads.
@@ -142,13 +231,7 @@ __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, i
     }
   } else {
     const uint8_t* base = a.W + ((size_t)strip * a.n_rec + rec) * Fmt<FMT>::REC_BYTES;
-    if constexpr (NT) {
-      r.w = __builtin_nontemporal_load((const u4*)(base + lane * 16));
-      if constexpr (FMT == FMT_FP425) r.t = __builtin_nontemporal_load(base + 1024 + lane);
-    } else {
-      r.w = *(const u4*)(base + lane * 16);
-      if constexpr (FMT == FMT_FP425) r.t = base[1024 + lane];
-    }
+    load_lane_rec<FMT, NT>(r, base, lane);
   }
 }
 
@@ -157,23 +240,14 @@ __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, i
 template <int FMT, int MT>
 __device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x0, const _Float16* x1, f4 acc[MT]) {
   h8 a[Fmt<FMT>::N_MFMA];
-  if constexpr (FMT == FMT_FP425) {
-    const uint32_t spread = spread_shared_fp425((uint32_t)r.t);
-#pragma unroll
-    for (int d = 0; d < 4; d++) {
-      uint32_t o[4];
-      restore_fp425(r.w[d], shared_of_word_fp425(spread, d), o);
-      a[d] = __builtin_bit_cast(h8, u4{o[0], o[1], o[2], o[3]});
-    }
-  } else if constexpr (FMT == FMT_FP533) {
-    uint32_t o[12];
-#pragma unroll
-    for (int d = 0; d < 4; d++) restore_fp533(r.w[d], &o[3 * d]);
-#pragma unroll
-    for (int u = 0; u < 3; u++) a[u] = __builtin_bit_cast(h8, u4{o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]});
-  } else {
+  if constexpr (FMT == FMT_FP16) {
 #pragma unroll
     for (int d = 0; d < 4; d++) a[d] = __builtin_bit_cast(h8, r.w[d]);
+  } else {
+    uint32_t o[4 * Fmt<FMT>::N_MFMA];
+    restore_rec<FMT>(r, o);
+#pragma unroll
+    for (int u = 0; u < Fmt<FMT>::N_MFMA; u++) a[u] = __builtin_bit_cast(h8, u4{o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]});
   }
 #pragma unroll
   for (int u = 0; u < Fmt<FMT>::N_MFMA; u++) {
@@ -187,14 +261,15 @@ __device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x
 // Operand slot of activation k (relative to its record) in LDS.
 template <int FMT>
 __device__ __forceinline__ int x_slot(int kk) {
-  if constexpr (FMT == FMT_FP425) {
-    return (kk & ~7) + 2 * (kk & 3) + ((kk >> 2) & 1);
-  } else if constexpr (FMT == FMT_FP533) {
-    const int q = kk / 6, r = kk - 6 * q;
-    const int h = r >= 3 ? 1 : 0;
-    return 6 * q + 2 * (r - 3 * h) + h;
-  } else {
+  if constexpr (FMT == FMT_FP16) {
     return kk;
+  } else {
+    constexpr int PB = Fmt<FMT>::PB;
+    const int blk = kk / PB, j = kk - blk * PB;
+    int slot = 0;
+    for (int s = 0; s < PB; s++)
+      if (slot_channel<FMT>(s) == j) slot = s;
+    return blk * PB + slot;
   }
 }
 
@@ -205,6 +280,19 @@ __device__ __forceinline__ uint32_t pick2(const uint32_t* in, int ia, int ib) {
   return __builtin_amdgcn_perm(in[ib >> 1], in[ia >> 1], sel);
 }
 
+// One permutation block of activations from input-channel order into operand order
+// (packed pairs in, packed pairs out).
+template <int FMT>
+__device__ __forceinline__ void permute_unit(const uint32_t (&in)[Fmt<FMT>::PB / 2], uint32_t (&out)[Fmt<FMT>::PB / 2]) {
+#pragma unroll
+  for (int m = 0; m < Fmt<FMT>::PB / 2; m++) {
+    if constexpr (FMT == FMT_FP16)
+      out[m] = in[m];
+    else
+      out[m] = pick2(in, slot_channel<FMT>(2 * m), slot_channel<FMT>(2 * m + 1));
+  }
+}
+
 // Activation staging.  A wave copies X[0..M) x [k0, k0+nk) into its LDS region in operand
 // order (zero beyond K), nk a multiple of the record size.  The copy is split in a load
 // half (global -> registers, no control flow around the loads) and a store half
@@ -213,7 +301,7 @@ __device__ __forceinline__ uint32_t pick2(const uint32_t* in, int ia, int ib) {
 // u & (2^x_shift - 1) (rows are padded to a power of two of units).
 template <int FMT>
 struct XUnit {
-  static constexpr int UNIT = FMT == FMT_FP533 ? 24 : 8;  // halfs permuted together
+  static constexpr int UNIT = Fmt<FMT>::PB;               // halfs permuted together
   static constexpr int CH = UNIT / 8;                     // 16-byte chunks per unit
   static constexpr int XU = 2;                            // units a lane moves per pass
 };
@@ -259,18 +347,7 @@ __device__ __forceinline__ void x_store(const XRegs<FMT>& xr, _Float16* xs, cons
       in[4 * e] = xr.c[i][e][0] & keep, in[4 * e + 1] = xr.c[i][e][1] & keep;
       in[4 * e + 2] = xr.c[i][e][2] & keep, in[4 * e + 3] = xr.c[i][e][3] & keep;
     }
-    if constexpr (FMT == FMT_FP425) {
-#pragma unroll
-      for (int t = 0; t < 4; t++) out[t] = pick2(in, t, t + 4);
-    } else if constexpr (FMT == FMT_FP533) {
-#pragma unroll
-      for (int q = 0; q < 4; q++)
-#pragma unroll
-        for (int t = 0; t < 3; t++) out[3 * q + t] = pick2(in, 6 * q + t, 6 * q + 3 + t);
-    } else {
-#pragma unroll
-      for (int t = 0; t < 4; t++) out[t] = in[t];
-    }
+    permute_unit<FMT>(in, out);
     if (m < a.M && j < upr) {
       u4* dst = (u4*)(xs + m * a.x_stride + UNIT * j);
 #pragma unroll
@@ -477,18 +554,7 @@ __device__ __forceinline__ void stage_x_block(_Float16* xs, const LinearArgs& a,
       const u4 c = k + 8 * e < a.K ? *(const u4*)(src + 8 * e) : u4{0, 0, 0, 0};
       in[4 * e] = c[0], in[4 * e + 1] = c[1], in[4 * e + 2] = c[2], in[4 * e + 3] = c[3];
     }
-    if constexpr (FMT == FMT_FP425) {
-#pragma unroll
-      for (int t = 0; t < 4; t++) out[t] = pick2(in, t, t + 4);
-    } else if constexpr (FMT == FMT_FP533) {
-#pragma unroll
-      for (int q = 0; q < 4; q++)
-#pragma unroll
-        for (int t = 0; t < 3; t++) out[3 * q + t] = pick2(in, 6 * q + t, 6 * q + 3 + t);
-    } else {
-#pragma unroll
-      for (int t = 0; t < 4; t++) out[t] = in[t];
-    }
+    permute_unit<FMT>(in, out);
     u4* dst = (u4*)(xs + m * a.x_stride + UNIT * j);
 #pragma unroll
     for (int e = 0; e < CH; e++) dst[e] = u4{out[4 * e], out[4 * e + 1], out[4 * e + 2], out[4 * e + 3]};
@@ -856,7 +922,8 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
   if (rec_id >= total_recs) return;
   const int strip = (int)(rec_id / n_rec), rec = (int)(rec_id - (int64_t)strip * n_rec);
   const uint8_t* base = W + (size_t)rec_id * Fmt<FMT>::REC_BYTES;
-  const u4 w = *(const u4*)(base + lane * 16);
+  LaneRec<FMT> r;
+  load_lane_rec<FMT, false>(r, base, lane);
   const int n = strip * 16 + (lane & 15);
   if (n >= N) return;
   float mul = kTwo14;
@@ -870,29 +937,15 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
       out[(size_t)n * K + k] = (uint16_t)(__builtin_bit_cast(uint16_t, (_Float16)v) | (bits16 & 0x8000));
     }
   };
-  if constexpr (FMT == FMT_FP425) {
-    const uint32_t spread = spread_shared_fp425(base[1024 + lane]);
+  uint32_t o[4 * Fmt<FMT>::N_MFMA];
+  restore_rec<FMT>(r, o);
+  constexpr int PB = Fmt<FMT>::PB;
 #pragma unroll
-    for (int d = 0; d < 4; d++) {
-      uint32_t o[4];
-      restore_fp425(w[d], shared_of_word_fp425(spread, d), o);
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        put(kbase + 8 * d + i, o[i] & 0xFFFF);
-        put(kbase + 8 * d + 4 + i, o[i] >> 16);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int d = 0; d < 4; d++) {
-      uint32_t o[3];
-      restore_fp533(w[d], o);
-#pragma unroll
-      for (int i = 0; i < 3; i++) {
-        put(kbase + 6 * d + i, o[i] & 0xFFFF);
-        put(kbase + 6 * d + 3 + i, o[i] >> 16);
-      }
-    }
+  for (int m = 0; m < 4 * Fmt<FMT>::N_MFMA; m++) {
+    // pair m = operand slots 2m and 2m+1 of the lane chunk
+    const int blk = (2 * m) / PB * PB;
+    put(kbase + blk + slot_channel<FMT>(2 * m - blk), o[m] & 0xFFFF);
+    put(kbase + blk + slot_channel<FMT>(2 * m + 1 - blk), o[m] >> 16);
   }
 }
 
@@ -936,11 +989,14 @@ struct Plan {
 // draining in lockstep.
 constexpr int kResidentWaves = 4096;
 
+// activations are staged in units of one permutation block
+int x_unit(int fmt) { return fmt == FMT_FP16 ? 8 : ams::kFormats[fmt].perm_block; }
+
 Plan make_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
   Plan p;
   const int mt = M > 16 ? 2 : 1;
   const int64_t total_recs = n_strips * n_rec;
-  const int lr_max = fmt == FMT_FP16 ? 4 : 8;  // the baseline's records are four times larger
+  const int lr_max = 4;
   const int per_wave_target = (int)std::min<int64_t>(n_rec, std::max<int64_t>(2, (total_recs + kResidentWaves - 1) / kResidentWaves));
   int S = std::min(16, std::max(1, (n_rec + per_wave_target - 1) / per_wave_target));
   S = std::min(S, n_rec);
@@ -965,7 +1021,7 @@ Plan make_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
     S = S / 2;
   }
   {
-    const int units = p.x_phase * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    const int units = p.x_phase * rec_k / x_unit(fmt);
     p.x_shift = 0;
     while ((1 << p.x_shift) < units) p.x_shift++;
   }
@@ -1016,7 +1072,7 @@ StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec
     // measured on the Llama-8B/70B shapes: deeper rings only lengthen the drain at the end of the stream
     p.lr = fmt == FMT_FP16 ? 2 : 4;  // the baseline's records are four times larger
     while (p.lr > 2 && p.lr > per_wave_max) p.lr /= 2;
-    const int units = rc * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    const int units = rc * rec_k / x_unit(fmt);
     p.x_shift = 0;
     while ((1 << p.x_shift) < units) p.x_shift++;
     break;
@@ -1056,7 +1112,7 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k
     p.x_stride = x_stride;
     p.x_region = M * x_stride;
     p.lds = lds;
-    const int units = rc * rec_k / (fmt == FMT_FP533 ? 24 : 8);
+    const int units = rc * rec_k / x_unit(fmt);
     p.x_shift = 0;
     while ((1 << p.x_shift) < units) p.x_shift++;
     break;
@@ -1103,13 +1159,11 @@ int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, 
     }
   } else if (kind == kStream) {
     switch (lr) {
-      case 8: if constexpr (FMT != FMT_FP16) return launch(stream_kernel<FMT, MT, 8>, a, grid, S, lds, st); break;
       case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
       case 2: return launch(stream_kernel<FMT, MT, 2>, a, grid, S, lds, st);
     }
   } else {
     switch (lr) {
-      case 8: if constexpr (FMT != FMT_FP16) return launch(phase_kernel<FMT, MT, 8>, a, grid, S, lds, st); break;
       case 4: return launch(phase_kernel<FMT, MT, 4>, a, grid, S, lds, st);
       case 2: return launch(phase_kernel<FMT, MT, 2>, a, grid, S, lds, st);
     }
@@ -1195,19 +1249,30 @@ int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t*
   const int64_t total = ((N + 15) / 16) * n_rec;
   const unsigned grid = (unsigned)((total + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
-  if (fmt == FMT_FP533)
-    hipLaunchKernelGGL(dequant_kernel<FMT_FP533>, dim3(grid), dim3(256), 0, st, (const uint8_t*)W_packed, scales, W_out,
-                       (int)N, (int)K, n_rec, total, scaled);
-  else
-    hipLaunchKernelGGL(dequant_kernel<FMT_FP425>, dim3(grid), dim3(256), 0, st, (const uint8_t*)W_packed, scales, W_out,
-                       (int)N, (int)K, n_rec, total, scaled);
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint8_t*)W_packed, scales, W_out, (int)N, (int)K, n_rec, total, scaled);
+  };
+  switch (fmt) {
+    case FMT_FP533: go(dequant_kernel<FMT_FP533>); break;
+    case FMT_FP425: go(dequant_kernel<FMT_FP425>); break;
+    case FMT_FP45: go(dequant_kernel<FMT_FP45>); break;
+    case FMT_FP433: go(dequant_kernel<FMT_FP433>); break;
+    case FMT_FP6: go(dequant_kernel<FMT_FP6>); break;
+    default: go(dequant_kernel<FMT_FP5>); break;
+  }
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
 int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K,
                int fmt, void* stream) {
-  if (fmt == FMT_FP533) return run_linear<FMT_FP533>(W_packed, scales, X, Y, M, N, K, stream);
-  if (fmt == FMT_FP425) return run_linear<FMT_FP425>(W_packed, scales, X, Y, M, N, K, stream);
+  switch (fmt) {
+    case FMT_FP533: return run_linear<FMT_FP533>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP425: return run_linear<FMT_FP425>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP45: return run_linear<FMT_FP45>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream);
+  }
   return AMS_ERR_FORMAT;
 }
 

@@ -6,30 +6,44 @@
 // same information is kept here, but arranged for 64-wide wavefronts feeding
 // 16x16x32 fp16 MFMA tiles:
 //
-//   * rows are cut into strips of 16 output channels, K into records of
-//     REC_K weights (96 for FP5.33, 128 for FP4.25);
-//   * a record is 64 lane chunks of 16 bytes, lane l = row (l & 15) of the strip,
-//     K-quarter (l >> 4) of the record, so one wavefront load of a record is one
-//     contiguous 1 KiB dwordx4 access and every lane already owns the operand slots
-//     of its MFMA row;
-//   * FP4.25 records carry 64 more bytes: lane l's byte holds the shared bits of its
-//     8 groups (the "1 word of shared LSBs per 64 weights" of Sec. 3.2, kept per lane);
+//   * rows are cut into strips of 16 output channels, K into records of REC_K weights
+//     (96 for the formats whose lane chunk holds 24 weights, 128 for those with 32);
+//   * a record starts with 64 lane chunks (16 bytes, 12 for FP4.33), lane l = row
+//     (l & 15) of the strip, K-quarter (l >> 4) of the record, so one wavefront load
+//     of a record is one contiguous dwordx4 (dwordx3) access and every lane already
+//     owns the operand slots of its MFMA row;
+//   * formats whose last mantissa bits do not fit in the chunk carry them behind the
+//     chunks, 1, 2 or 4 bytes per lane (the "word of shared LSBs" of Sec. 3.2, kept
+//     per lane so that no cross-lane traffic is needed);
 //   * the records of a strip are contiguous, strips follow each other.
 //
-// Inside a lane chunk each 32-bit word holds two groups, A in the low half-word and B
-// in the high half-word, and the restored fp16 pairs are (A_i, B_i): that way the two
-// shared bits of a pair sit 16 bits apart and one shift+mask places both.
+// A lane chunk is made of 32-bit words of two half-words (A low, B high); a half-word
+// holds the remainders (code without its last bit) of 4 weights (e2m2: 4 bits each) or
+// 3 weights (e2m3: 5 bits each, plus one spare bit).  The restored fp16 pairs are
+// (A_i, B_i), so the last bits of a pair sit 16 bits apart and one shift+mask places
+// both.  Half-word layouts (bit 15 .. bit 0), chosen so that sign and magnitude land on
+// fp16 bit 15 and bits 11.. with the fewest VALU operations:
+//   e2m2:  s0 s2 s3 s1 | mag0(3) | mag1(3) | mag2(3) | mag3(3)       mag = e1 e0 m1
+//   e2m3:  s0 s1 s2 b  | mag0(4) | mag1(4) | mag2(4)                 mag = e1 e0 m2 m1
+// (b = the group's shared bit for FP5.33, the last bit of member 0 for FP6).
+//
+// Which weights of a lane chunk form a sharing group (they are always k consecutive
+// input channels, Sec. 3.1) and where their common last bit is kept:
+//   FP4.25 (k=4)  the 4 members of a half-word; side byte, bit 4h + d
+//   FP5.33 (k=3)  the 3 members of a half-word; bit 12 of the half-word
+//   FP4.5  (k=2)  member i of half h in words 2q and 2q+1; side byte q, bit 4h + i
+//   FP4.33 (k=3)  member i of half h in words 0, 1, 2;      side byte, bit 4h + i
+//   FP5    (k=1)  every weight its own bit;                 side byte d, bit 4h + i
+//   FP6    (k=1)  member 0: bit 12 of its half-word; members 1, 2: side 16 bits,
+//                 bit 8h + 2d + (i - 1)
+// With the groups of FP4.5 / FP4.33 running across words, the last bits needed for the
+// four restored pairs of a word are the same for all words of the group.
 //
 // Restored values are produced as fp16 bit patterns equal to value * 2^-14: the
 // bias-1 exponent and the mantissa are dropped into the low exponent bits / high
 // mantissa bits of binary16 (bias 15), which maps subnormal codes onto fp16
 // subnormals (Sec. 3.2's SHIFT/AND/OR restoration).  The factor 2^14 is applied in
 // fp32 together with the row scale.
-//
-// Half-word layouts (bit 15 .. bit 0), chosen so that sign and magnitude fields land
-// on fp16 bit 15 and bits 11.. with the fewest VALU operations:
-//   FP4.25:  s0 s2 s3 s1 | mag0(3) | mag1(3) | mag2(3) | mag3(3)      mag = e1 e0 m1
-//   FP5.33:  s0 s1 s2 sh | mag0(4) | mag1(4) | mag2(4)                mag = e1 e0 m2 m1
 #ifndef AMS_LAYOUT_H_
 #define AMS_LAYOUT_H_
 
@@ -38,39 +52,78 @@
 namespace ams {
 
 constexpr int kStripRows = 16;
-constexpr int kLaneChunkBytes = 16;
 constexpr int kLanes = 64;
 
+// format numbers of the C ABI
+constexpr int kFmtFp533 = 0, kFmtFp425 = 1, kFmtFp45 = 2, kFmtFp433 = 3, kFmtFp6 = 4, kFmtFp5 = 5, kNumFormats = 6;
+
 struct FormatInfo {
-  int group;       // weights sharing one last mantissa bit
-  int code_bits;   // bits of a full code (sign + 2 exponent + mantissa)
-  int rec_k;       // weights of one row inside a record
-  int lane_k;      // weights of one lane chunk (rec_k / 4)
-  int rec_bytes;   // bytes of a record
-  double fmax;     // largest magnitude of the format
+  int group;        // weights sharing one last mantissa bit
+  int code_bits;    // bits of a full code (sign + 2 exponent + mantissa)
+  int rec_k;        // weights of one row inside a record
+  int lane_k;       // weights of one lane chunk (rec_k / 4)
+  int chunk_bytes;  // bytes of a lane chunk
+  int side_bytes;   // bytes per lane behind the chunks
+  int rec_bytes;    // bytes of a record = 64 * (chunk_bytes + side_bytes)
+  int perm_block;   // operand slots and input channels are permuted inside blocks of this many weights
+  double fmax;      // largest magnitude of the format
 };
 
-constexpr FormatInfo kFp533 = {3, 6, 96, 24, 1024, 7.5};
-constexpr FormatInfo kFp425 = {4, 5, 128, 32, 1024 + 64, 7.0};
+constexpr FormatInfo kFormats[kNumFormats] = {
+    {3, 6, 96, 24, 16, 0, 1024, 24, 7.5},   // FP5.33-e2m3
+    {4, 5, 128, 32, 16, 1, 1088, 8, 7.0},   // FP4.25-e2m2
+    {2, 5, 128, 32, 16, 2, 1152, 16, 7.0},  // FP4.5-e2m2
+    {3, 5, 96, 24, 12, 1, 832, 24, 7.0},    // FP4.33-e2m2
+    {1, 6, 96, 24, 16, 2, 1152, 24, 7.5},   // FP6-e2m3
+    {1, 5, 128, 32, 16, 4, 1280, 8, 7.0},   // FP5-e2m2
+};
 
-inline const FormatInfo* format_info(int fmt) {
-  if (fmt == 0) return &kFp533;
-  if (fmt == 1) return &kFp425;
-  return nullptr;
-}
+inline const FormatInfo* format_info(int fmt) { return fmt >= 0 && fmt < kNumFormats ? &kFormats[fmt] : nullptr; }
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
-// Position of logical weight j (0..lane_k-1) of a lane chunk inside the lane's MFMA
-// operand order: the restored pairs come out as (A_i, B_i) per 32-bit word, so the
-// activations must be laid out in the same order.  Both functions are bijections of
-// [0, lane_k).
-//   FP4.25: word d = j/8, group half h = (j%8)/4, member i = j%4 -> slot 8d + 2i + h
-//   FP5.33: word d = j/6, group half h = (j%6)/3, member i = j%3 -> slot 6d + 2i + h
-inline int operand_slot_fp425(int j) { return (j & ~7) + 2 * (j & 3) + ((j >> 2) & 1); }
-inline int operand_slot_fp533(int j) {
-  int d = j / 6, r = j % 6;
-  return 6 * d + 2 * (r % 3) + r / 3;
+// Where weight j (0 .. lane_k-1, in input-channel order) of a lane chunk lives.
+struct Place {
+  int d, h, i;  // 32-bit word, half-word (0 = A), member inside the half-word
+};
+constexpr Place place(int fmt, int j) {
+  switch (fmt) {
+    case kFmtFp533:
+    case kFmtFp6: return {j / 6, (j % 6) / 3, j % 3};
+    case kFmtFp433: return {j % 3, (j / 3) / 4, (j / 3) % 4};
+    case kFmtFp45: return {2 * (j / 16) + j % 2, ((j % 16) / 2) / 4, ((j % 16) / 2) % 4};
+    default: return {j / 8, (j % 8) / 4, j % 4};  // FP4.25, FP5
+  }
+}
+
+// Position of that weight in the lane's MFMA operand order (the activations are laid
+// out in the same order): the restored pairs of a word come out as (A_i, B_i).
+constexpr int operand_slot(int fmt, int j) {
+  const Place p = place(fmt, j);
+  return (fmt == kFmtFp533 || fmt == kFmtFp6) ? 2 * (3 * p.d + p.i) + p.h : 8 * p.d + 2 * p.i + p.h;
+}
+
+// The inverse inside one permutation block: input channel (relative to the block) of
+// operand slot s (relative to the block).
+constexpr int slot_channel(int fmt, int s) {
+  const int pb = kFormats[fmt].perm_block;
+  for (int j = 0; j < pb; j++)
+    if (operand_slot(fmt, j) == s) return j;
+  return -1;
+}
+
+// Bit of the lane's side bytes (taken as one little-endian integer) that holds the last
+// mantissa bit of weight j, or -1 when it is kept in the half-word itself.
+constexpr int side_bit(int fmt, int j) {
+  const Place p = place(fmt, j);
+  switch (fmt) {
+    case kFmtFp425: return 4 * p.h + p.d;
+    case kFmtFp433: return 4 * p.h + p.i;
+    case kFmtFp45: return 8 * (p.d / 2) + 4 * p.h + p.i;
+    case kFmtFp5: return 8 * p.d + 4 * p.h + p.i;
+    case kFmtFp6: return p.i == 0 ? -1 : 8 * p.h + 2 * p.d + (p.i - 1);
+    default: return -1;  // FP5.33: bit 12 of the half-word
+  }
 }
 
 }  // namespace ams

@@ -12,7 +12,8 @@ from paper_2510_16045_amd import synth
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
-PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]
+PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]  # the two formats the paper builds kernels for
+PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2)]
 REL_L2_TOL = 1e-3
 MAX_ABS_TOL = 2e-2  # relative to rms(Y_ref)
 
@@ -45,6 +46,9 @@ def test_dequant_every_code_through_the_kernel(fmt, ofmt):
         for shift in range(g):
             rem = (np.arange(nrem * g) // 1 + shift * 7) % nrem
             rows.append(((rem << 1) | sh).astype(np.uint8))
+    if g == 1:  # no sharing: every full code in every position of a lane chunk
+        for shift in range(0, 33, 1):
+            rows.append(((np.arange(nrem) * 2 + shift * 3 + (np.arange(nrem) // 3)) % (2 * nrem)).astype(np.uint8))
     codes = np.stack(rows)
     codes = np.tile(codes, (3, 2))[:, : codes.shape[1] * 2 - 5]  # ragged tail, several strips' worth of rows
     lsb = codes[:, ::g][:, : -(-codes.shape[1] // g)] & 1
@@ -156,7 +160,7 @@ def test_linear_full_size_sampled_rows(fmt, ofmt):
     assert np.all(np.isfinite(y))
 
 
-@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("fmt,ofmt", PAPER_PAIRS + [(ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3)])
 @pytest.mark.parametrize(
     "N,K,Ms",
     [
@@ -201,10 +205,10 @@ def test_device_entry_points_reject_bad_arguments():
     p = lambda t: t.data_ptr()
     assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 0, 16, 96, 0, None) == -2
     assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 33, 16, 96, 0, None) == -2
-    assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 1, 16, 96, 5, None) == -1
+    assert lib.ams_linear(p(wp), p(sc), p(x), p(y), 1, 16, 96, 9, None) == -1
     assert lib.ams_linear(None, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -3
     assert lib.ams_linear(p(wp) + 2, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -4
-    assert lib.ams_dequant(3, p(wp), p(sc), p(y), 16, 96, 1, None) == -1
+    assert lib.ams_dequant(9, p(wp), p(sc), p(y), 16, 96, 1, None) == -1
     assert lib.ams_fp16_linear(p(x), p(x), p(y), 1, 1, 95, None) == -2
     assert lib.ams_read_probe(None, 1024, None, None) == -3
     assert lib.ams_read_probe(p(wp) + 2, 1024, None, None) == -4

@@ -14,7 +14,9 @@ from oracle import ams_oracle as O
 from paper_2510_16045_amd import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]
+PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]  # the two formats the paper builds kernels for
+PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2)]
+REC = {ams.FP533: (96, 1024), ams.FP425: (128, 1088), ams.FP45: (128, 1152), ams.FP433: (96, 832), ams.FP6: (96, 1152), ams.FP5: (128, 1280)}
 
 
 def test_library_exports_every_declared_symbol():
@@ -27,20 +29,24 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
     assert lib.ams_version() >= 100
     assert lib.ams_strerror(0) == b"ok"
-    assert [lib.ams_group_size(f) for f in (0, 1, 7)] == [3, 4, 0]
-    assert [lib.ams_code_bits(f) for f in (0, 1, 7)] == [6, 5, 0]
+    assert [lib.ams_group_size(f) for f in range(8)] == [3, 4, 2, 3, 1, 1, 0, 0]
+    assert [lib.ams_code_bits(f) for f in range(8)] == [6, 5, 5, 5, 6, 5, 0, 0]
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
 @pytest.mark.parametrize("N,K", [(1, 1), (16, 96), (17, 100), (5, 13), (256, 768), (33, 1000)])
 def test_sizes(fmt, ofmt, N, K):
-    assert ams.ams_canonical_bytes(fmt, N, K) == O.canonical_packed_bytes(ofmt, N, K)
-    rec_k, rec_b = (96, 1024) if fmt == ams.FP533 else (128, 1088)
+    if (fmt, ofmt) in PAPER_PAIRS:
+        assert ams.ams_canonical_bytes(fmt, N, K) == O.canonical_packed_bytes(ofmt, N, K)
+    rec_k, rec_b = REC[fmt]
     want = (-(-N // 16)) * (-(-K // rec_k)) * rec_b
     assert ams.ams_packed_bytes(fmt, N, K) == want
-    # without padding the gfx950 layout takes exactly the bytes of the paper's packing
+    # a record holds exactly bits-per-weight * 16 * rec_k bits
+    assert rec_b * 8 == round(ofmt.bits_per_weight * 16 * rec_k)
+    # without padding the gfx950 layout takes exactly the bytes of the densest packing
     if N % 16 == 0 and K % rec_k == 0:
         assert ams.ams_packed_bytes(fmt, N, K) == ams.ams_canonical_bytes(fmt, N, K)
+        assert ams.ams_packed_bytes(fmt, N, K) * 8 == round(ofmt.bits_per_weight * N * K)
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
@@ -138,11 +144,19 @@ def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
     codes = ((rem << 1) | np.repeat(sh, g, axis=1)[:, :K]).astype(np.uint8)
     packed = ams.ams_pack_codes(fmt, codes)
     assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
-    # codes that went through the paper's own packing come back the same
-    via_paper = O.unpack_canonical(O.pack_canonical(codes, ofmt), ofmt, K).astype(np.uint8)
-    assert np.array_equal(ams.ams_unpack_host(fmt, ams.ams_pack_codes(fmt, via_paper), N, K), codes)
+    # every stored bit matters: flipping any bit of a record that holds no padding changes a code
+    if N % 16 == 0 and K % REC[fmt][0] == 0 and N * K <= 16 * 128:
+        for byte in range(0, packed.size, 7):
+            for bit in range(8):
+                p2 = packed.copy()
+                p2[byte] ^= 1 << bit
+                assert not np.array_equal(ams.ams_unpack_host(fmt, p2, N, K), codes), (byte, bit)
+    if (fmt, ofmt) in PAPER_PAIRS:
+        # codes that went through the paper's own packing come back the same
+        via_paper = O.unpack_canonical(O.pack_canonical(codes, ofmt), ofmt, K).astype(np.uint8)
+        assert np.array_equal(ams.ams_unpack_host(fmt, ams.ams_pack_codes(fmt, via_paper), N, K), codes)
     bad = codes.copy()
-    if K >= 2:
+    if K >= 2 and g > 1:
         bad[0, 0] ^= 1  # group 0 no longer agrees in its last bit
         with pytest.raises(ams.AmsError):
             ams.ams_pack_codes(fmt, bad)
@@ -150,7 +164,7 @@ def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
 
 def test_padding_is_zero_and_layout_is_deterministic():
     W = synth.gaussian_weights(5, 50, 3)
-    for fmt in (ams.FP533, ams.FP425):
+    for fmt, _ in PAIRS:
         a, _ = ams.ams_pack(fmt, W)
         b, _ = ams.ams_pack(fmt, W)
         assert np.array_equal(a, b)

@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
 # by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77689 + 56) * 1024}
-FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2"}
+FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2", 2: "fp4.5-e2m2", 3: "fp4.33-e2m2", 4: "fp6-e2m3", 5: "fp5-e2m2"}
 
 
 def parse_args():
@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--layers", default="8b", choices=["8b", "70b", "qwen"])
     ap.add_argument("--sweep", action="store_true", help="also run the batch sweep M=1..32")
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
+    ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all six formats (the step keeps the paper's two)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
                    
@@ -62,10 +63,10 @@ def to_dev(a, torch):
 class Layer:
     """One Linear: packed copies in both formats + fp16 copies, all resident in HBM."""
 
-    def __init__(self, name, N, K, W, ams, torch, n_copies, fp16_copies):
+    def __init__(self, name, N, K, W, ams, torch, n_copies, fp16_copies, fmts):
         self.name, self.N, self.K = name, N, K
         self.packed, self.scales, self.canon = {}, {}, {}
-        for fmt in (ams.FP533, ams.FP425):
+        for fmt in fmts:
             p, s = ams.ams_pack(fmt, W)
             base = to_dev(p, torch)
             self.packed[fmt] = [base] + [base.clone() for _ in range(n_copies - 1)]
@@ -167,7 +168,7 @@ def profile_kernel(args, shapes, torch, ams, synth):
         ws = [to_dev(W, torch) for _ in range(3)]
         run = lambda i: ams.ams_fp16_linear(ws[i % 3], x, out=y)
     else:
-        fmt = {"fp5.33": ams.FP533, "fp4.25": ams.FP425}[fmt_s]
+        fmt = {"fp5.33": ams.FP533, "fp4.25": ams.FP425, "fp4.5": ams.FP45, "fp4.33": ams.FP433, "fp6": ams.FP6, "fp5": ams.FP5}[fmt_s]
         p, s = ams.ams_pack(fmt, W)
         ps = [to_dev(p, torch) for _ in range(n_copies)]
         sc = to_dev(s, torch)
@@ -203,17 +204,18 @@ def main():
     set_bytes = sum(n * k * 16 // 3 // 8 for n, k in shapes.values())
     n_copies = max(2, -(-args.copies_mb * (1 << 20) // set_bytes))
     fp16_copies = max(2, -(-args.copies_mb * (1 << 20) // (3 * set_bytes)))
+    fmts = (ams.FP533, ams.FP425)  # the step: the two formats the paper builds kernels for
+    all_fmts = (ams.FP6, ams.FP533, ams.FP5, ams.FP45, ams.FP433, ams.FP425) if args.all_formats else fmts
     layers = []
     for i, (name, (N, K)) in enumerate(shapes.items()):
         W = maker(N, K, 100 + i)
-        layers.append(Layer(name, N, K, W, ams, torch, n_copies, fp16_copies))
+        layers.append(Layer(name, N, K, W, ams, torch, n_copies, fp16_copies, all_fmts))
         del W
     print(f"# setup {time.perf_counter() - t_setup:.1f}s, {n_copies} packed copies, {fp16_copies} fp16 copies per layer", file=sys.stderr)
 
     M = 1
     xs = {l.name: to_dev(synth.activations(M, l.K, 7), torch) for l in layers}
     ys = {l.name: torch.empty((M, l.N), dtype=torch.float16, device="cuda") for l in layers}
-    fmts = (ams.FP533, ams.FP425)
 
     def step(i):
         for l in layers:
@@ -248,7 +250,7 @@ def main():
     for l in layers:
         t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % fp16_copies], xs[l.name], out=ys[l.name]), n_launch)
         tlib = time_launches(torch, lambda i: torch.matmul(xs[l.name], l.w16[i % fp16_copies].t(), out=ys[l.name]), n_launch)
-        for fmt in fmts:
+        for fmt in all_fmts:
             t, pct = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch, replays=10, spread=True)
             warm = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
             # second denominator: a bare read of the same packed bytes (same rotation), nothing computed
@@ -269,9 +271,9 @@ def main():
             )
 
     # ---- roofline of the dominant kernel: the launch that moves the most bytes
-    dom = max(per_layer, key=lambda r: r["packed_bytes"])
+    dom = max((r for r in per_layer if r["fmt"] in (FMT_NAMES[0], FMT_NAMES[1])), key=lambda r: r["packed_bytes"])
     dl = next(l for l in layers if l.name == dom["layer"])
-    dfmt = ams.FP533 if dom["fmt"] == FMT_NAMES[0] else ams.FP425
+    dfmt = next(f for f, n in FMT_NAMES.items() if n == dom["fmt"])
     alg_bytes = dl.canon[dfmt] + 2 * dl.N + 2 * M * dl.K + 2 * M * dl.N
     t_dom = time_launches(torch, lambda i: ams.ams_linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, out=ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
@@ -294,7 +296,7 @@ def main():
                 y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
                 t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % fp16_copies], x, out=y), n_launch)
                 tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % fp16_copies].t(), out=y), n_launch)
-                for fmt in fmts:
+                for fmt in all_fmts:
                     t = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], x, l.N, fmt, out=y), n_launch)
                     sweep.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
                                   "GBps": round(l.canon[fmt] / t / 1e3, 1), "fp16_us": round(t16, 3),

@@ -352,23 +352,63 @@ def dequant_unscaled(codes: np.ndarray, fmt: Format) -> np.ndarray:
     return decode(codes, fmt).astype(np.float16)
 
 
-def dequant_real(codes: np.ndarray, s: np.ndarray, fmt: Format) -> np.ndarray:
+def per_weight_scales(s: np.ndarray, K: int, scale_group: int | None = None) -> np.ndarray:
+    """The scale of every weight as fp64 [N, K]: one per row (s is [N]) or one per
+    run of ``scale_group`` input channels of a row (s is [N, ceil(K / scale_group)])."""
+    s64 = np.asarray(s).astype(np.float64)
+    if s64.ndim == 1:
+        return np.repeat(s64[:, None], K, axis=1)
+    if scale_group is None or s64.shape[1] != -(-K // scale_group):
+        raise ValueError("grouped scales need the matching scale_group")
+    return np.repeat(s64, scale_group, axis=1)[:, :K]
+
+
+def dequant_real(codes: np.ndarray, s: np.ndarray, fmt: Format, scale_group: int | None = None) -> np.ndarray:
     """DeQ(W) = Q(W) * s (Eq. 2) in fp64, unrounded (the product is exact)."""
-    return decode(codes, fmt) * np.asarray(s).astype(np.float64)[:, None]
+    codes = np.asarray(codes)
+    return decode(codes, fmt) * per_weight_scales(s, codes.shape[1], scale_group)
 
 
-def dequant_scaled(codes: np.ndarray, s: np.ndarray, fmt: Format) -> np.ndarray:
+def dequant_scaled(codes: np.ndarray, s: np.ndarray, fmt: Format, scale_group: int | None = None) -> np.ndarray:
     """Eq. 2 rounded once to fp16 (round-to-nearest-even, subnormals kept)."""
-    return dequant_real(codes, s, fmt).astype(np.float16)
+    return dequant_real(codes, s, fmt, scale_group).astype(np.float16)
 
 
-def linear(codes: np.ndarray, s: np.ndarray, X: np.ndarray, fmt: Format) -> np.ndarray:
+def linear(codes: np.ndarray, s: np.ndarray, X: np.ndarray, fmt: Format, scale_group: int | None = None) -> np.ndarray:
     """Y[m,n] = sum_k DeQ(W)[n,k] * X[m,k] in fp64 (Eq. 2 then a plain matmul).
 
     X is the fp16 activation matrix [M,K] widened to fp64.
     """
     X64 = np.asarray(X).astype(np.float64)
-    return X64 @ dequant_real(codes, s, fmt).T
+    return X64 @ dequant_real(codes, s, fmt, scale_group).T
+
+
+def ams_quantize_grouped(W: np.ndarray, fmt: Format, scale_group: int, search: str = "set"):
+    """AMS quantization with one scale per run of ``scale_group`` input channels of a row.
+
+    Sec. 5 states that the method works at any granularity "from per-tensor and
+    per-channel to per-group"; only per-channel is spelled out (Sec. 3.1).  The
+    reading taken: Eq. 1 is applied to every run of ``scale_group`` consecutive
+    input channels of a row by itself (its own max |W| / M, rounded to fp16), the
+    sharing groups and the search stay inside a run (``scale_group`` must be a
+    multiple of the sharing group size), and everything else is as ams_quantize.
+    So the result is the per-channel method applied to each column block alone.
+
+    Returns (codes [N,K], scales [N, ceil(K/scale_group)] float16).
+    """
+    W = np.asarray(W)
+    N, K = W.shape
+    if scale_group <= 0 or scale_group % fmt.group != 0:
+        raise ValueError("scale_group must be a positive multiple of the sharing group size")
+    codes = np.empty((N, K), dtype=np.int64)
+    n_sg = -(-K // scale_group)
+    scales = np.empty((N, n_sg), dtype=np.float16)
+    for j in range(n_sg):
+        block = slice(j * scale_group, min(K, (j + 1) * scale_group))
+        c, s, _ = ams_quantize(np.ascontiguousarray(W[:, block]), fmt, search=search)
+        codes[:, block] = c
+        scales[:, j] = s
+    return codes, scales
 
 
 def fp16_linear(W: np.ndarray, X: np.ndarray) -> np.ndarray:

@@ -290,6 +290,63 @@ def test_reround_search_is_optimal_over_all_codes_with_a_common_last_bit(fmt):
             assert abs(mine - best) <= 1e-12 * max(best, 1e-300)
 
 
+# ---- one scale per run of input channels (Sec. 5: "any granularity") ---------------------------
+@pytest.mark.parametrize("fmt", AMS + [O.FP45, O.FP433, O.FP6_E2M3])
+def test_grouped_scales_definition(fmt):
+    N, K, sg = 5, 100, 12 * fmt.group
+    W = synth.heavy_tail_weights(N, K, 91)
+    codes, s = O.ams_quantize_grouped(W, fmt, sg)
+    n_sg = -(-K // sg)
+    assert s.shape == (N, n_sg) and codes.shape == (N, K)
+    W64 = W.astype(np.float64)
+    fmax = O.format_max(fmt)
+    for n in range(N):
+        for j in range(n_sg):
+            blk = W64[n, j * sg : (j + 1) * sg]
+            want = np.float16(np.max(np.abs(blk)) / fmax)  # Eq. 1 on the run alone
+            assert s[n, j] == (want if want != 0 else np.float16(1.0))
+    # sharing groups stay inside a run and still agree in their last bit
+    g = fmt.group
+    for k0 in range(0, K, g):
+        assert np.all((codes[:, k0 : k0 + g] & 1) == (codes[:, k0 : k0 + 1] & 1))
+    # Eq. 2 with the run's scale, scalar arithmetic
+    deq = O.dequant_real(codes, s, fmt, sg)
+    sign_bit = fmt.code_bits - 1
+    for n in range(N):
+        for k in range(K):
+            c = int(codes[n, k])
+            v = O.magnitude_of(c & (fmt.n_mag - 1), fmt.mbits)
+            v = -v if (c >> sign_bit) & 1 else v
+            assert deq[n, k] == v * float(s[n, k // sg])
+    # and a plain matmul on top of it
+    X = synth.activations(3, K, 92)
+    Y = O.linear(codes, s, X, fmt, sg)
+    for m in range(3):
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                acc += deq[n, k] * float(X[m, k])
+            assert abs(Y[m, n] - acc) <= 1e-12 * max(1.0, abs(acc))
+
+
+@pytest.mark.parametrize("fmt", AMS)
+def test_grouped_scales_reduce_to_per_channel_and_help_on_heavy_tails(fmt):
+    W = synth.heavy_tail_weights(16, 768, 93)
+    c_row, s_row, _ = O.ams_quantize(W, fmt)
+    c_one, s_one = O.ams_quantize_grouped(W, fmt, 768)  # one run = the whole row
+    assert np.array_equal(c_row, c_one) and np.array_equal(s_row, s_one[:, 0])
+    c_big, s_big = O.ams_quantize_grouped(W, fmt, 1200)  # a run longer than the row
+    assert np.array_equal(c_row, c_big) and np.array_equal(s_row, s_big[:, 0])
+    W64 = W.astype(np.float64)
+    mse = lambda c, s_, sg: float(np.mean((O.dequant_real(c, s_, fmt, sg) - W64) ** 2))
+    c96, s96 = O.ams_quantize_grouped(W, fmt, 96)
+    assert mse(c96, s96, 96) < mse(c_row, s_row, None)
+    with pytest.raises(ValueError):
+        O.ams_quantize_grouped(W, fmt, fmt.group + 1)
+    with pytest.raises(ValueError):
+        O.dequant_real(c96, s96, fmt, 128)
+
+
 def test_worked_groups_fixture():
     names = {"fp4.25": O.FP425, "fp5.33": O.FP533}
     n = 0

@@ -113,6 +113,29 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W_fp16, int64_t N, int64_t 
                 uint16_t* scales_fp16, uint8_t* codes);
 
 /*
+ * One scale per run of `scale_group` consecutive input channels of a row instead of
+ * one per row (Sec. 5: the method "can be applied with any granularity ... per-group";
+ * read as Eq. 1, RTN and the search applied to every run by itself).  scale_group must
+ * be the record size of the format (96 for FP5.33 / FP4.33 / FP6, 128 for the others)
+ * times a power of two; the last run of a row may be shorter.
+ *   ams_group_scales_count  number of fp16 scales: ceil(K / scale_group) per row, rows
+ *                           padded to a multiple of 16
+ *   ams_pack_grouped        as ams_pack_ex; `scales_fp16` receives that many values in
+ *                           the order the kernels read them: [strip of 16 rows][run][row
+ *                           inside the strip] (1.0 for padding rows)
+ *   ams_dequant_grouped / ams_linear_grouped
+ *                           as ams_dequant / ams_linear with such a scale buffer (device)
+ * Errors: as their per-row counterparts; SHAPE for a scale_group that is not allowed.
+ */
+int ams_group_scales_count(int fmt, int64_t N, int64_t K, int64_t scale_group, size_t* count);
+int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W_fp16, int64_t N, int64_t K, int64_t ldw,
+                     void* packed, uint16_t* scales_fp16, uint8_t* codes);
+int ams_dequant_grouped(int fmt, const void* W_packed, const uint16_t* scales, int64_t scale_group, uint16_t* W_out_fp16,
+                        int64_t N, int64_t K, int scaled, void* stream);
+int ams_linear_grouped(const void* W_packed, const uint16_t* scales, int64_t scale_group, const uint16_t* X, uint16_t* Y,
+                       int M, int64_t N, int64_t K, int fmt, void* stream);
+
+/*
  * Pack codes that were produced elsewhere (e.g. read from the paper's layout) into
  * the gfx950 layout.  codes [N, K] as written by ams_pack; within a group all last
  * bits must agree (else AMS_ERR_SHAPE).  Host pointers.

@@ -50,6 +50,10 @@ def load_library():
     lib.ams_canonical_bytes.argtypes = [_int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.ams_pack.argtypes = [_int, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
     lib.ams_pack_ex.argtypes = [_int, _int, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
+    lib.ams_group_scales_count.argtypes = [_int, _i64, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
+    lib.ams_pack_grouped.argtypes = [_int, _int, _i64, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
+    lib.ams_dequant_grouped.argtypes = [_int, _vp, _vp, _i64, _vp, _i64, _i64, _int, _vp]
+    lib.ams_linear_grouped.argtypes = [_vp, _vp, _i64, _vp, _vp, _int, _i64, _i64, _int, _vp]
     lib.ams_pack_codes.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_unpack_host.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_dequant.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _int, _vp]
@@ -200,3 +204,56 @@ def ams_read_probe(buf, nbytes: int = None):
     if nbytes > buf.numel() * buf.element_size():
         raise ValueError("nbytes exceeds the buffer")
     _check(load_library().ams_read_probe(_dev_ptr(buf), nbytes, None, _stream()), "ams_read_probe")
+
+
+def ams_group_scales_count(fmt: int, N: int, K: int, scale_group: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().ams_group_scales_count(fmt, N, K, scale_group, ctypes.byref(out)), "ams_group_scales_count")
+    return out.value
+
+
+def ams_pack_grouped(fmt: int, W: np.ndarray, scale_group: int, search: int = SEARCH_SET_BIT, return_codes: bool = False):
+    """Quantize + pack with one scale per run of scale_group input channels.  The scales come back in the
+    order the kernels read them: [strip of 16 rows, run, row inside the strip]."""
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array")
+    W = np.ascontiguousarray(W)
+    N, K = W.shape
+    packed = np.empty(ams_packed_bytes(fmt, N, K), dtype=np.uint8)
+    n_sg = -(-K // scale_group)
+    scales = np.empty(ams_group_scales_count(fmt, N, K, scale_group), dtype=np.float16).reshape(-1, n_sg, 16)
+    codes = np.empty((N, K), dtype=np.uint8) if return_codes else None
+    rc = load_library().ams_pack_grouped(fmt, search, scale_group, _np_ptr(W), N, K, K, _np_ptr(packed), _np_ptr(scales), _np_ptr(codes) if return_codes else None)
+    _check(rc, "ams_pack_grouped")
+    return (packed, scales, codes) if return_codes else (packed, scales)
+
+
+def ams_dequant_grouped(fmt: int, W_packed, scales, scale_group: int, N: int, K: int, scaled: bool = True, out=None):
+    import torch
+
+    if W_packed.numel() != ams_packed_bytes(fmt, N, K):
+        raise ValueError("packed buffer has the wrong size")
+    if scales.numel() != ams_group_scales_count(fmt, N, K, scale_group):
+        raise ValueError("scale buffer has the wrong size")
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=W_packed.device)
+    rc = load_library().ams_dequant_grouped(fmt, _dev_ptr(W_packed, torch.uint8), _dev_ptr(scales, torch.float16), scale_group, _dev_ptr(out, torch.float16), N, K, int(scaled), _stream())
+    _check(rc, "ams_dequant_grouped")
+    return out
+
+
+def ams_linear_grouped(W_packed, scales, scale_group: int, X, N: int, fmt: int, out=None):
+    import torch
+
+    M, K = X.shape
+    if W_packed.numel() != ams_packed_bytes(fmt, N, K):
+        raise ValueError("packed buffer has the wrong size")
+    if scales.numel() != ams_group_scales_count(fmt, N, K, scale_group):
+        raise ValueError("scale buffer has the wrong size")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = load_library().ams_linear_grouped(
+        _dev_ptr(W_packed, torch.uint8), _dev_ptr(scales, torch.float16), scale_group, _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K, fmt, _stream()
+    )
+    _check(rc, "ams_linear_grouped")
+    return out

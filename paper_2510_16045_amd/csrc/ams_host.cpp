@@ -314,6 +314,59 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, in
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
 }
 
+// log2(scale_group / rec_k), or -1 when scale_group is not rec_k * 2^j
+int scale_group_shift(const FormatInfo& fi, int64_t scale_group) {
+  for (int j = 0; j < 20; j++)
+    if (scale_group == (int64_t)fi.rec_k << j) return j;
+  return -1;
+}
+
+int ams_group_scales_count(int fmt, int64_t N, int64_t K, int64_t scale_group, size_t* count) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (!count) return AMS_ERR_NULL;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  if (scale_group_shift(fi, scale_group) < 0) return AMS_ERR_SHAPE;
+  *count = (size_t)(ams::round_up(N, ams::kStripRows)) * (size_t)((K + scale_group - 1) / scale_group);
+  return AMS_OK;
+}
+
+int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W, int64_t N, int64_t K, int64_t ldw,
+                     void* packed, uint16_t* scales, uint8_t* codes_out) {
+  if (int rc = check_shape(fmt, N, K)) return rc;
+  if (search != AMS_SEARCH_SET_BIT && search != AMS_SEARCH_REROUND) return AMS_ERR_SHAPE;
+  if (!W || !packed || !scales) return AMS_ERR_NULL;
+  if (ldw < K) return AMS_ERR_SHAPE;
+  const FormatInfo& fi = *ams::format_info(fmt);
+  if (scale_group_shift(fi, scale_group) < 0) return AMS_ERR_SHAPE;
+  const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax, search};
+  const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
+  const int64_t n_sg = (K + scale_group - 1) / scale_group;
+  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
+  std::atomic<int> bad{0};
+  parallel_for(n_strips, [&](int64_t t) {
+    std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
+    const uint8_t* rows[16];
+    for (int r = 0; r < 16; r++) {
+      const int64_t n = t * 16 + r;
+      uint16_t* srow = scales + (size_t)t * n_sg * 16 + r;  // [strip][run][row in strip]
+      if (n >= N) {
+        rows[r] = nullptr;
+        for (int64_t j = 0; j < n_sg; j++) srow[j * 16] = 0x3C00;  // padding rows: 1.0
+        continue;
+      }
+      uint8_t* c = buf.data() + (size_t)r * K;
+      for (int64_t j = 0; j < n_sg; j++) {  // Eq. 1 and the search on every run by itself
+        const int64_t a = j * scale_group, len = std::min<int64_t>(scale_group, K - a);
+        if (!quantize_row(rq, W + n * ldw + a, len, c + a, srow + j * 16)) bad.store(1);
+      }
+      rows[r] = c;
+      if (codes_out) std::memcpy(codes_out + n * K, c, (size_t)K);
+    }
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+  });
+  return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
+}
+
 int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* packed) {
   if (int rc = check_shape(fmt, N, K)) return rc;
   if (!codes || !packed) return AMS_ERR_NULL;

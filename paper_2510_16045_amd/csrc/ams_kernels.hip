@@ -28,6 +28,7 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef unsigned short us4 __attribute__((ext_vector_type(4)));
 
 constexpr int FMT_FP533 = AMS_FMT_FP533_E2M3;
 constexpr int FMT_FP425 = AMS_FMT_FP425_E2M2;
@@ -152,6 +153,7 @@ struct LinearArgs {
   int red_slots; // stream kernel: partial tiles a wave may park in LDS (strips its piece can touch)
   int piece_q, piece_r;  // stream kernel: pairs per wave in a full workgroup: quotient, remainder
   int rc;                // stream kernel: records per strip in one phase of K
+  int n_sg, sg_shift;    // scales per run of input channels: runs per row, log2(records per run)
 };
 
 // One lane's part of the record at `base`: its chunk (one dwordx4, or three dwords that the
@@ -758,7 +760,7 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
 // order, scaled, converted, stored.  The activations are staged once per workgroup in LDS
 // in operand order; when M x K does not fit, K is walked in phases of rc records per strip
 // and the parked tiles accumulate over the phases.  The grid is one resident round.
-template <int FMT, int MT, int LR, bool NT>
+template <int FMT, int MT, int LR, bool NT, bool GS = false>
 __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
@@ -788,7 +790,9 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
   const int chunk_k = RC * REC_K;
   // Scales of the first strip this wave finishes: requested first, kept as raw bits until the epilogue.
-  const ScaleBits scale0_bits = load_scale_bits<FMT>(a, min(g + min(wave, ns - 1) * G, a.n_strips - 1), lane);
+  // (With one scale per run of input channels, GS, the scales travel with the records instead.)
+  ScaleBits scale0_bits = {{0x3C00, 0x3C00, 0x3C00, 0x3C00}};
+  if constexpr (!GS) scale0_bits = load_scale_bits<FMT>(a, min(g + min(wave, ns - 1) * G, a.n_strips - 1), lane);
   __builtin_amdgcn_sched_barrier(0);
 
   // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
@@ -824,9 +828,15 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     // before, then works on its own (a refill into the slot being read would have to wait
     // until the restoration has consumed it).
     constexpr int RS = LR + 1;
-    LaneRec<FMT> ring[RS];
-    auto request = [&](LaneRec<FMT>& slot) {
-      load_rec<FMT, NT>(slot, a, g + pj * G, rec_base + pr, lane);
+    struct Slot {
+      LaneRec<FMT> r;
+      us4 gs;  // GS: the scales of this lane's four output channels for the record's run
+    };
+    Slot ring[RS];
+    auto request = [&](Slot& slot) {
+      load_rec<FMT, NT>(slot.r, a, g + pj * G, rec_base + pr, lane);
+      if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
+        slot.gs = *(const us4*)(a.scales + ((size_t)(g + pj * G) * a.n_sg + ((rec_base + pr) >> a.sg_shift)) * 16 + 4 * kq);
       if (pf + S < total) {
         pf += S, pr += S;
         while (pr >= n_rec) pr -= n_rec, pj++;
@@ -866,10 +876,22 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     };
     // One record: request the one LR ahead, multiply, move on by S records; where that leaves
     // the strip, the tile is parked.  Only the request touches global memory.
-    auto step = [&](LaneRec<FMT>& slot, LaneRec<FMT>& free_slot) {
+    auto step = [&](Slot& slot, Slot& free_slot) {
       request(free_slot);
       __builtin_amdgcn_sched_barrier(0);
-      mac_rec<FMT, MT>(slot, x0 + cr * REC_K, x1 + cr * REC_K, acc);
+      if constexpr (GS) {  // the record's own tile, times its run's scales (Eq. 2), then into the sum
+        f4 t[MT];
+#pragma unroll
+        for (int i = 0; i < MT; i++) t[i] = f4{0, 0, 0, 0};
+        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, t);
+        f4 sc;
+#pragma unroll
+        for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)slot.gs[r]);
+#pragma unroll
+        for (int i = 0; i < MT; i++) acc[i] += t[i] * sc;
+      } else {
+        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc);
+      }
       pending = true;
       cr += S;
       if (cr >= n_rec) {
@@ -909,14 +931,19 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
       }
     }
     const int strip = g + j * G;
-    store_tile_scaled<MT>(sum, j == wave ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip, lane), a, strip, lane);
+    f4 sc;
+    if constexpr (GS)
+      sc = f4{kTwo14, kTwo14, kTwo14, kTwo14};
+    else
+      sc = j == wave ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip, lane);
+    store_tile_scaled<MT>(sum, sc, a, strip, lane);
   }
 }
 
 // Restore a whole packed matrix to row-major fp16: one wavefront per record.
 template <int FMT>
 __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const uint16_t* scales, uint16_t* out, int N, int K,
-                                                      int n_rec, int64_t total_recs, int scaled) {
+                                                      int n_rec, int64_t total_recs, int scaled, int n_sg, int sg_shift) {
   const int lane = threadIdx.x & 63;
   const int64_t rec_id = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (rec_id >= total_recs) return;
@@ -927,7 +954,8 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
   const int n = strip * 16 + (lane & 15);
   if (n >= N) return;
   float mul = kTwo14;
-  if (scaled) mul *= (float)__builtin_bit_cast(_Float16, scales[n]);
+  // one scale per row (sg_shift < 0) or per run of 2^sg_shift records: [strip][run][row in strip]
+  if (scaled) mul *= (float)__builtin_bit_cast(_Float16, sg_shift < 0 ? scales[n] : scales[((size_t)strip * n_sg + (rec >> sg_shift)) * 16 + (lane & 15)]);
   const int kbase = rec * Fmt<FMT>::REC_K + (lane >> 4) * (Fmt<FMT>::REC_K / 4);
   auto put = [&](int k, uint32_t bits16) {
     if (k < K) {
@@ -1089,24 +1117,28 @@ struct SweepPlan {
 // Launch shape of the sweeping kernel: one resident round of workgroups of up to 16
 // wavefronts; LDS holds one parked tile per (strip, wave) and the activations of one
 // phase of K, in as few phases as fit.
-SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
+// any_shape: this kernel must take the shape (no other kernel can): strips per workgroup
+// are capped so that the parked tiles fit, whatever number of rounds and phases that takes.
+SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, bool any_shape = false) {
   SweepPlan p;
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
   p.ok = false;
-  if (n_strips > (int64_t)kNumCU * 64) return p;
+  if (!any_shape && n_strips > (int64_t)kNumCU * 64) return p;
   p.spw = (int)((n_strips + kNumCU - 1) / kNumCU);
+  const size_t tile_bytes = (size_t)mt * 4 * mc * 16;  // one parked tile
+  if (any_shape) p.spw = (int)std::max<int64_t>(1, std::min<int64_t>(p.spw, (64 * 1024) / (16 * tile_bytes)));
   p.grid = (int)((n_strips + p.spw - 1) / p.spw);
   p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * n_rec);
   p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
-  const size_t parts = (size_t)p.spw * p.S * mt * 4 * mc * 16;
-  for (int n_phase = 1; n_phase <= 8 && n_phase <= n_rec; n_phase++) {
+  const size_t parts = (size_t)p.spw * p.S * tile_bytes;
+  for (int n_phase = 1; n_phase <= (any_shape ? n_rec : 8) && n_phase <= n_rec; n_phase++) {
     const int rc = (n_rec + n_phase - 1) / n_phase;
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
     const size_t lds = (size_t)M * x_stride * 2 + parts;
     if (lds > (size_t)kStreamLdsMax) continue;
     // measured: with many parked tiles and more than two phases the contiguous-piece kernel is faster
-    if (n_phase > 2 && parts > 32 * 1024) break;
+    if (!any_shape && n_phase > 2 && parts > 32 * 1024) break;
     p.ok = true;
     p.rc = rc;
     p.x_stride = x_stride;
@@ -1146,11 +1178,13 @@ int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hip
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
-enum KernelKind { kSweep, kSweepCached, kStream, kPhase };
+enum KernelKind { kSweep, kSweepCached, kSweepGrouped, kStream, kPhase };
 
 template <int FMT, int MT>
 int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
-  if (kind == kSweep || kind == kSweepCached) {
+  if (kind == kSweepGrouped) {
+    if constexpr (FMT != FMT_FP16) return launch(sweep_kernel<FMT, MT, 2, true, true>, a, grid, S, lds, st);
+  } else if (kind == kSweep || kind == kSweepCached) {
     if constexpr (FMT == FMT_FP16) {
       if (lr == 1) return launch(sweep_kernel<FMT, MT, 1, false>, a, grid, S, lds, st);
     } else {
@@ -1173,7 +1207,7 @@ int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, 
 
 template <int FMT>
 int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K,
-               void* stream) {
+               void* stream, int64_t scale_group = 0) {
   if (!W || !X || !Y || (FMT != FMT_FP16 && !scales)) return AMS_ERR_NULL;
   if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (FMT == FMT_FP16 && (K % 8) != 0) return AMS_ERR_SHAPE;
@@ -1192,7 +1226,18 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.n_rec = n_rec;
   a.n_strips = (int)n_strips;
   hipStream_t st = (hipStream_t)stream;
-  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K);
+  a.n_sg = 0;
+  a.sg_shift = 0;
+  if (scale_group != 0) {  // one scale per run of scale_group = REC_K * 2^shift input channels
+    int shift = -1;
+    for (int j = 0; j < 20; j++)
+      if (scale_group == (int64_t)REC_K << j) shift = j;
+    if (shift < 0 || FMT == FMT_FP16) return AMS_ERR_SHAPE;
+    a.sg_shift = shift;
+    a.n_sg = (int)((K + scale_group - 1) / scale_group);
+  }
+  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, scale_group != 0);
+  if (scale_group != 0 && !wp.ok) return AMS_ERR_SHAPE;
   if (wp.ok) {
     a.x_stride = wp.x_stride;
     a.x_region = wp.x_region;
@@ -1203,7 +1248,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.piece_q = a.piece_r = 0;
     a.rc = wp.rc;
     // measured: below about 24 MB of packed weights ordinary loads win, above that non-temporal ones
-    const KernelKind kind = n_strips * n_rec * (int64_t)Fmt<FMT>::REC_BYTES < (24ll << 20) ? kSweepCached : kSweep;
+    const KernelKind kind = scale_group != 0 ? kSweepGrouped
+                            : n_strips * n_rec * (int64_t)Fmt<FMT>::REC_BYTES < (24ll << 20) ? kSweepCached : kSweep;
     return M <= 16 ? launch_by_ring<FMT, 1>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st)
                    : launch_by_ring<FMT, 2>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st);
   }
@@ -1240,17 +1286,30 @@ extern "C" {
 
 int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t* W_out, int64_t N, int64_t K, int scaled,
                 void* stream) {
+  return ams_dequant_grouped(fmt, W_packed, scales, 0, W_out, N, K, scaled, stream);
+}
+
+int ams_dequant_grouped(int fmt, const void* W_packed, const uint16_t* scales, int64_t scale_group, uint16_t* W_out,
+                        int64_t N, int64_t K, int scaled, void* stream) {
   const ams::FormatInfo* fi = ams::format_info(fmt);
   if (!fi) return AMS_ERR_FORMAT;
   if (!W_packed || !W_out || (scaled && !scales)) return AMS_ERR_NULL;
   if (N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (!aligned16(W_packed)) return AMS_ERR_ALIGN;
+  int sg_shift = -1, n_sg = 0;  // per-row scales
+  if (scale_group != 0) {
+    for (int j = 0; j < 20; j++)
+      if (scale_group == (int64_t)fi->rec_k << j) sg_shift = j;
+    if (sg_shift < 0) return AMS_ERR_SHAPE;
+    n_sg = (int)((K + scale_group - 1) / scale_group);
+  }
   const int n_rec = (int)((K + fi->rec_k - 1) / fi->rec_k);
   const int64_t total = ((N + 15) / 16) * n_rec;
   const unsigned grid = (unsigned)((total + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
   auto go = [&](auto kern) {
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint8_t*)W_packed, scales, W_out, (int)N, (int)K, n_rec, total, scaled);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint8_t*)W_packed, scales, W_out, (int)N, (int)K, n_rec, total, scaled, n_sg,
+                       sg_shift);
   };
   switch (fmt) {
     case FMT_FP533: go(dequant_kernel<FMT_FP533>); break;
@@ -1272,6 +1331,20 @@ int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, 
     case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream);
     case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream);
     case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream);
+  }
+  return AMS_ERR_FORMAT;
+}
+
+int ams_linear_grouped(const void* W_packed, const uint16_t* scales, int64_t scale_group, const uint16_t* X, uint16_t* Y,
+                       int M, int64_t N, int64_t K, int fmt, void* stream) {
+  if (scale_group <= 0) return AMS_ERR_SHAPE;
+  switch (fmt) {
+    case FMT_FP533: return run_linear<FMT_FP533>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP425: return run_linear<FMT_FP425>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP45: return run_linear<FMT_FP45>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
   }
   return AMS_ERR_FORMAT;
 }

@@ -113,6 +113,43 @@ def test_reround_packed_weights_through_the_kernels(fmt, ofmt):
     check_linear(y, O.linear(codes, o_scales, X, ofmt), "reround")
 
 
+REC_K = {ams.FP533: 96, ams.FP425: 128, ams.FP45: 128, ams.FP433: 96, ams.FP6: 96, ams.FP5: 128}
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("N,K,mult,Ms", [(100, 1030, 1, (1, 3)), (48, 14336, 2, (1, 16)), (528, 4096, 1, (4, 32)), (16, 5, 1, (1,))])
+def test_grouped_scales_through_the_kernels(fmt, ofmt, N, K, mult, Ms):
+    # one scale per run of input channels: restored weights bit for bit, Linear within tolerance
+    sg = REC_K[fmt] * mult
+    W = synth.heavy_tail_weights(N, K, 47)
+    packed, scales = ams.ams_pack_grouped(fmt, W, sg)
+    codes, o_scales = O.ams_quantize_grouped(W, ofmt, sg)
+    wp, sc = dev(packed), dev(scales)
+    got = host16(ams.ams_dequant_grouped(fmt, wp, sc, sg, N, K, scaled=True))
+    assert np.array_equal(got.view(np.uint16), O.dequant_scaled(codes, o_scales, ofmt, sg).view(np.uint16))
+    for M in Ms:
+        X = synth.activations(M, K, 48 + M)
+        y = host16(ams.ams_linear_grouped(wp, sc, sg, dev(X), N, fmt))
+        check_linear(y, O.linear(codes, o_scales, X, ofmt, sg), f"grouped N={N} K={K} M={M}")
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAPER_PAIRS)
+def test_grouped_scales_large_shape_sampled_rows(fmt, ofmt):
+    # many strips per workgroup; at M=32 the strips per workgroup are capped and the grid takes several rounds
+    N, K = 28672, 4096
+    sg = REC_K[fmt]
+    W = synth.gaussian_weights(N, K, 83)
+    packed, scales = ams.ams_pack_grouped(fmt, W, sg)
+    wp, sc = dev(packed), dev(scales)
+    rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(7, N, 131), 16 * 255 : 16 * 257 + 1])
+    codes, o_scales = O.ams_quantize_grouped(W[rows], ofmt, sg)
+    for M in (1, 8, 32):
+        X = synth.activations(M, K, 84 + M)
+        y = host16(ams.ams_linear_grouped(wp, sc, sg, dev(X), N, fmt)).astype(np.float64)
+        assert np.all(np.isfinite(y))
+        check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt, sg), f"grouped large M={M}")
+
+
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_linear_heavy_tail_weights_and_outlier_activations(fmt, ofmt):
     N, K = 64, 8192
@@ -210,6 +247,8 @@ def test_device_entry_points_reject_bad_arguments():
     assert lib.ams_linear(p(wp) + 2, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -4
     assert lib.ams_dequant(9, p(wp), p(sc), p(y), 16, 96, 1, None) == -1
     assert lib.ams_fp16_linear(p(x), p(x), p(y), 1, 1, 95, None) == -2
+    assert lib.ams_linear_grouped(p(wp), p(sc), 100, p(x), p(y), 1, 16, 96, 0, None) == -2
+    assert lib.ams_dequant_grouped(0, p(wp), p(sc), 95, p(y), 16, 96, 1, None) == -2
     assert lib.ams_read_probe(None, 1024, None, None) == -3
     assert lib.ams_read_probe(p(wp) + 2, 1024, None, None) == -4
     torch.cuda.synchronize()

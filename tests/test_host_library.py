@@ -115,6 +115,29 @@ def test_reround_search_on_every_fp16_value(fmt, ofmt):
         assert np.array_equal(codes, o_codes.astype(np.uint8))
 
 
+def rowmajor_scales(scales_dev: np.ndarray, N: int) -> np.ndarray:
+    """[strip, run, row in strip] -> [N, runs]"""
+    return scales_dev.transpose(0, 2, 1).reshape(-1, scales_dev.shape[1])[:N]
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize("N,K,mult,search", [(40, 1000, 1, "set"), (16, 768, 2, "reround"), (3, 100, 4, "set")])
+def test_grouped_scales_match_oracle_bit_for_bit(fmt, ofmt, N, K, mult, search):
+    sg = REC[fmt][0] * mult
+    W = synth.heavy_tail_weights(N, K, 27)
+    packed, scales, codes = ams.ams_pack_grouped(fmt, W, sg, search=ams.SEARCH_REROUND if search == "reround" else ams.SEARCH_SET_BIT, return_codes=True)
+    o_codes, o_scales = O.ams_quantize_grouped(W, ofmt, sg, search=search)
+    assert scales.shape == (-(-N // 16), -(-K // sg), 16)
+    assert np.array_equal(rowmajor_scales(scales, N).view(np.uint16), o_scales.view(np.uint16))
+    pad = scales.transpose(0, 2, 1).reshape(-1, scales.shape[1])[N:]
+    assert np.all(pad == np.float16(1.0))
+    assert np.array_equal(codes, o_codes.astype(np.uint8))
+    assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
+    for bad in (sg + 1, sg * 3, REC[fmt][0] // 2, 0, -96):
+        with pytest.raises(ams.AmsError):
+            ams.ams_group_scales_count(fmt, N, K, bad)
+
+
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_degenerate_rows_and_errors(fmt, ofmt):
     W = np.zeros((3, 24), dtype=np.float16)

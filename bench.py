@@ -46,6 +46,7 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true", help="also run the batch sweep M=1..32")
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
     ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all six formats (the step keeps the paper's two)")
+    ap.add_argument("--group-scales", action="store_true", help="also time ams_linear_grouped (one scale per record-sized run of K) per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
                    
@@ -74,6 +75,7 @@ class Layer:
             self.canon[fmt] = ams.ams_canonical_bytes(fmt, N, K)
         w = to_dev(W, torch)
         self.w16 = [w] + [w.clone() for _ in range(fp16_copies - 1)]
+        self.W = W  # host copy, for the variants packed on demand
 
 
 def time_launches(torch, fn, n_launch, warm=2, replays=5, spread=False):
@@ -255,12 +257,22 @@ def main():
             warm = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
             # second denominator: a bare read of the same packed bytes (same rotation), nothing computed
             t_read = time_launches(torch, lambda i: ams.ams_read_probe(l.packed[fmt][i % n_copies]), n_launch)
+            t_grouped = None
+            if args.group_scales:
+                sg = 96 if fmt in (ams.FP533, ams.FP433, ams.FP6) else 128
+                gp, gs = ams.ams_pack_grouped(fmt, l.W, sg)
+                gpd = [to_dev(gp, torch)]
+                gpd += [gpd[0].clone() for _ in range(n_copies - 1)]
+                gsd = to_dev(gs.reshape(-1), torch)
+                t_grouped = time_launches(torch, lambda i: ams.ams_linear_grouped(gpd[i % n_copies], gsd, sg, xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
+                del gpd, gsd
             gbps = l.canon[fmt] / t / 1e3
             per_layer.append(
                 {
                     "layer": l.name, "N": l.N, "K": l.K, "M": M, "fmt": FMT_NAMES[fmt],
                     "us": round(t, 3), "us_percentiles": pct, "us_cache_resident": round(warm, 3),
                     "bare_read_us": round(t_read, 3), "frac_of_bare_read": round(t_read / t, 4),
+                    "us_group_scales": None if t_grouped is None else round(t_grouped, 3),
                     "packed_bytes": l.canon[fmt], "allocated_bytes": ams.ams_packed_bytes(fmt, l.N, l.K),
                     "GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
                     "fp16_us": round(t16, 3), "fp16_GBps": round(2 * l.N * l.K / t16 / 1e3, 1),

@@ -172,6 +172,24 @@ int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, 
 int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* stream);
 
 /*
+ * ams_linear / ams_fp16_linear with a workspace (device, 16-byte aligned, at least
+ * ams_linear_workspace_bytes() bytes, zero-filled once before its first use; the calls
+ * leave it ready for the next one, of any shape).  With a workspace the kernel may cut K in slices
+ * handled by different workgroups, which exchange fp32 partial tiles through it: shapes
+ * with few output channels (e.g. the MLP down-projections of Sec. 4.2's table, N = 2560
+ * to 5120) then use all compute units, and large batches stage less of X per workgroup.
+ * Results differ from ams_linear only in the order of the fp32 sums (deterministic for a
+ * given shape).  A workspace that is NULL or too small gives the behaviour of ams_linear.
+ * Calls that overlap in time must not share a workspace.
+ *   ams_linear_workspace_bytes  fmt = AMS_FMT_*, or -1 for the fp16 baseline; may return 0
+ */
+int ams_linear_workspace_bytes(int fmt, int M, int64_t N, int64_t K, size_t* bytes);
+int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
+                  int64_t K, int fmt, void* workspace, size_t workspace_bytes, void* stream);
+int ams_fp16_linear_ws(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid, not part of the method: a bare streaming read of the first
  * floor(bytes / 1024) KiB of `buf` (device, 16-byte aligned) in the order the Linear
  * kernel sweeps a packed matrix, nothing computed, nothing stored.  Its time is the

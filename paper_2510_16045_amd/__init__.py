@@ -59,6 +59,9 @@ def load_library():
     lib.ams_dequant.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _int, _vp]
     lib.ams_linear.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp]
     lib.ams_fp16_linear.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp]
+    lib.ams_linear_workspace_bytes.argtypes = [_int, _int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
+    lib.ams_linear_ws.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp, ctypes.c_size_t, _vp]
+    lib.ams_fp16_linear_ws.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp, ctypes.c_size_t, _vp]
     lib.ams_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
     _lib = lib
     return lib
@@ -256,4 +259,47 @@ def ams_linear_grouped(W_packed, scales, scale_group: int, X, N: int, fmt: int, 
         _dev_ptr(W_packed, torch.uint8), _dev_ptr(scales, torch.float16), scale_group, _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K, fmt, _stream()
     )
     _check(rc, "ams_linear_grouped")
+    return out
+
+
+def ams_linear_workspace_bytes(fmt: int, M: int, N: int, K: int) -> int:
+    """Bytes of workspace ams_linear_ws wants for this shape (fmt = -1: the fp16 baseline); may be 0."""
+    out = ctypes.c_size_t(0)
+    _check(load_library().ams_linear_workspace_bytes(fmt, M, N, K, ctypes.byref(out)), "ams_linear_workspace_bytes")
+    return out.value
+
+
+def ams_linear_ws(W_packed, scales, X, N: int, fmt: int, workspace, out=None):
+    """ams_linear with a workspace (a zero-filled uint8 CUDA tensor, reusable from call to call)."""
+    import torch
+
+    M, K = X.shape
+    if W_packed.numel() != ams_packed_bytes(fmt, N, K):
+        raise ValueError("packed buffer has the wrong size")
+    if scales.numel() != N:
+        raise ValueError("scales must have N entries")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = load_library().ams_linear_ws(
+        _dev_ptr(W_packed, torch.uint8), _dev_ptr(scales, torch.float16), _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K, fmt,
+        _dev_ptr(workspace, torch.uint8) if workspace is not None else None, workspace.numel() if workspace is not None else 0, _stream()
+    )
+    _check(rc, "ams_linear_ws")
+    return out
+
+
+def ams_fp16_linear_ws(W, X, workspace, out=None):
+    import torch
+
+    N, K = W.shape
+    M = X.shape[0]
+    if X.shape[1] != K:
+        raise ValueError("X and W disagree in K")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = load_library().ams_fp16_linear_ws(
+        _dev_ptr(W, torch.float16), _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K,
+        _dev_ptr(workspace, torch.uint8) if workspace is not None else None, workspace.numel() if workspace is not None else 0, _stream()
+    )
+    _check(rc, "ams_fp16_linear_ws")
     return out

@@ -154,6 +154,11 @@ struct LinearArgs {
   int piece_q, piece_r;  // stream kernel: pairs per wave in a full workgroup: quotient, remainder
   int rc;                // stream kernel: records per strip in one phase of K
   int n_sg, sg_shift;    // scales per run of input channels: runs per row, log2(records per run)
+  // split of K over gk workgroups per strip (sweep kernel with a workspace): workgroups along N,
+  // slices of K, per-slice partial tiles [gk][strip][MT][64] f4, per-strip arrival counters
+  int gn, gk;
+  f4* ws_tiles;
+  unsigned* ws_count;
 };
 
 // One lane's part of the record at `base`: its chunk (one dwordx4, or three dwords that the
@@ -765,14 +770,20 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
-               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc));
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = nthr >> 6;
-  const int G = gridDim.x, g = blockIdx.x;
+  // workgroup = (position g along N, slice gk of K); without a split the grid is all along N
+  const int G = a.gn;
+  const int gk = a.gk > 1 ? (int)(blockIdx.x / (unsigned)G) : 0;
+  const int g = (int)blockIdx.x - gk * G;
   const int ns = (a.n_strips - g + G - 1) / G;  // strips of this workgroup (>= 1)
   const int RC = a.rc;                          // records per strip in one phase of K
-  const bool one_phase = RC >= a.n_rec;
+  // records [rec_lo, rec_hi) of every strip are this workgroup's slice of K
+  const int rec_lo = a.gk > 1 ? (int)((unsigned)(gk * a.n_rec) / (unsigned)a.gk) : 0;
+  const int rec_hi = a.gk > 1 ? (int)((unsigned)((gk + 1) * a.n_rec) / (unsigned)a.gk) : a.n_rec;
+  const bool one_phase = RC >= rec_hi - rec_lo;
   const int mc = min(a.M, 16);  // activation rows of an MFMA tile that exist
   _Float16* xs = (_Float16*)smem;
   f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][S][MT][4 K-quarters][mc]
@@ -796,11 +807,11 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   __builtin_amdgcn_sched_barrier(0);
 
   // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
-  for (int rec_base = 0; rec_base < a.n_rec; rec_base += RC) {
-    const int n_rec = min(RC, a.n_rec - rec_base);                // records per strip in this phase
+  for (int rec_base = rec_lo; rec_base < rec_hi; rec_base += RC) {
+    const int n_rec = min(RC, rec_hi - rec_base);                 // records per strip in this phase
     const int total = ns * n_rec;                                 // records of this workgroup
     const int cnt = wave < total ? (total - wave + S - 1) / S : 0;  // records of this wave
-    if (rec_base > 0) __syncthreads();  // everyone is done with the previous phase's activations
+    if (rec_base > rec_lo) __syncthreads();  // everyone is done with the previous phase's activations
     const int k0 = rec_base * REC_K;
 
     // Activations: units beyond the first pass (large M) and unaligned rows are staged by loops
@@ -850,7 +861,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
 
     // while those are in flight: every tile slot cleared (a wave need not meet every strip when a
     // strip has fewer records than the workgroup has waves)
-    if (rec_base == 0)
+    if (rec_base == rec_lo)
       for (int i = tid; i < ns * S * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
     if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
     __syncthreads();
@@ -931,6 +942,29 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
       }
     }
     const int strip = g + j * G;
+    if (a.gk > 1) {
+      // K is split over gk workgroups: every one leaves its partial tile in the workspace and
+      // counts itself in; the one that arrives last adds all gk tiles in slice order (so the
+      // result does not depend on who was last), finishes the strip and clears the counter
+      // for the next call.  Nobody waits for anybody.
+      f4* wt = a.ws_tiles + ((size_t)gk * a.n_strips + strip) * MT * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < MT; t++) wt[t * 64] = sum[t];
+      __threadfence();  // the tile is visible device-wide before the count
+      unsigned before = 0;
+      if (lane == 0) before = atomicAdd(a.ws_count + strip, 1u);
+      before = __builtin_amdgcn_readfirstlane(before);
+      if (before != (unsigned)a.gk - 1) continue;
+      __threadfence();  // the others' tiles are visible before they are read
+#pragma unroll
+      for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+      for (int q = 0; q < a.gk; q++) {
+        const f4* rt = a.ws_tiles + ((size_t)q * a.n_strips + strip) * MT * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < MT; t++) sum[t] += rt[t * 64];
+      }
+      if (lane == 0) a.ws_count[strip] = 0;
+    }
     f4 sc;
     if constexpr (GS)
       sc = f4{kTwo14, kTwo14, kTwo14, kTwo14};
@@ -1110,7 +1144,7 @@ StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec
 
 struct SweepPlan {
   bool ok;
-  int S, lr, spw, grid, rc, x_shift, x_stride, x_region;
+  int S, lr, spw, grid, gn, gk, rc, x_shift, x_stride, x_region;
   size_t lds;
 };
 
@@ -1119,17 +1153,23 @@ struct SweepPlan {
 // phase of K, in as few phases as fit.
 // any_shape: this kernel must take the shape (no other kernel can): strips per workgroup
 // are capped so that the parked tiles fit, whatever number of rounds and phases that takes.
-SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, bool any_shape = false) {
+// gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
+SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, bool any_shape = false, int gk = 1) {
   SweepPlan p;
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
   p.ok = false;
+  p.gk = gk;
   if (!any_shape && n_strips > (int64_t)kNumCU * 64) return p;
-  p.spw = (int)((n_strips + kNumCU - 1) / kNumCU);
+  const int n_rec = (n_rec_all + gk - 1) / gk;  // records of the longest slice
+  const int wg_along_n = kNumCU / gk;
+  p.spw = (int)((n_strips + wg_along_n - 1) / wg_along_n);
   const size_t tile_bytes = (size_t)mt * 4 * mc * 16;  // one parked tile
   if (any_shape) p.spw = (int)std::max<int64_t>(1, std::min<int64_t>(p.spw, (64 * 1024) / (16 * tile_bytes)));
-  p.grid = (int)((n_strips + p.spw - 1) / p.spw);
-  p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * n_rec);
+  p.gn = (int)((n_strips + p.spw - 1) / p.spw);
+  p.grid = p.gn * gk;
+  p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * (n_rec_all / gk));  // n_rec_all / gk: the shortest slice
+  if (p.S < 1) return p;
   p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
   const size_t parts = (size_t)p.spw * p.S * tile_bytes;
   for (int n_phase = 1; n_phase <= (any_shape ? n_rec : 8) && n_phase <= n_rec; n_phase++) {
@@ -1150,6 +1190,37 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k
     break;
   }
   return p;
+}
+
+// Workspace of a split in gk slices: per-strip arrival counters, then the partial tiles.  The
+// counter area has one size for every shape, so that a workspace that is reused for another
+// shape never finds old tile data where it expects counters at zero.
+constexpr int64_t kSplitMaxStrips = 16384;
+constexpr size_t kSplitCounterBytes = (size_t)kSplitMaxStrips * 4;
+size_t split_workspace_bytes(int M, int64_t n_strips, int gk) {
+  return gk <= 1 ? 0 : kSplitCounterBytes + (size_t)gk * n_strips * (M > 16 ? 2 : 1) * 1024;
+}
+
+// How many slices of K to use when a workspace is available.  A split pays when the strips
+// alone do not fill the compute units evenly (e.g. 320 strips: 2 per workgroup on 160 CUs,
+// against 5 strips x a quarter of K on 256) and when the batch is large (every workgroup
+// stages the activations of its own slice of K only).  The estimate is bytes a workgroup
+// moves: its weight records, half weight for the activations it stages (they come from
+// L2), and a fixed charge for the exchange through the workspace.
+int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec_bytes) {
+  int best = 1;
+  double best_cost = 0;
+  for (int gk = 1; gk <= 8; gk *= 2) {
+    if (gk > 1 && (n_rec / gk < 8 || n_strips > kSplitMaxStrips)) break;
+    const SweepPlan p = make_sweep_plan(fmt, M, n_strips, n_rec, rec_k, false, gk);
+    if (!p.ok) continue;
+    const double slice = (double)((n_rec + gk - 1) / gk);
+    const double n_phase = std::max(1.0, slice / p.rc);
+    double cost = p.spw * slice * rec_bytes + 0.5 * M * slice * rec_k * 2 + 8192.0 * (n_phase - 1);
+    if (gk > 1) cost += 24576.0 + 2048.0 * gk * p.spw * (M > 16 ? 2 : 1);
+    if (best_cost == 0 || cost < best_cost) best = gk, best_cost = cost;
+  }
+  return best;
 }
 
 // Kernels that use more than 64 KiB of dynamic LDS must have their limit raised first;
@@ -1207,7 +1278,7 @@ int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, 
 
 template <int FMT>
 int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K,
-               void* stream, int64_t scale_group = 0) {
+               void* stream, int64_t scale_group = 0, void* workspace = nullptr, size_t ws_bytes = 0) {
   if (!W || !X || !Y || (FMT != FMT_FP16 && !scales)) return AMS_ERR_NULL;
   if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (FMT == FMT_FP16 && (K % 8) != 0) return AMS_ERR_SHAPE;
@@ -1236,9 +1307,26 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.sg_shift = shift;
     a.n_sg = (int)((K + scale_group - 1) / scale_group);
   }
-  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, scale_group != 0);
+  a.gn = 1;
+  a.gk = 1;
+  a.ws_tiles = nullptr;
+  a.ws_count = nullptr;
+  constexpr int REC_BYTES = FMT == FMT_FP16 ? 4096 : Fmt<FMT>::REC_BYTES;
+  int gk = 1;
+  if (workspace && scale_group == 0) {
+    if (!aligned16(workspace)) return AMS_ERR_ALIGN;
+    gk = choose_split(FMT, M, n_strips, n_rec, REC_K, REC_BYTES);
+    if (split_workspace_bytes(M, n_strips, gk) > ws_bytes) gk = 1;  // too small: no split
+  }
+  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, scale_group != 0, gk);
   if (scale_group != 0 && !wp.ok) return AMS_ERR_SHAPE;
   if (wp.ok) {
+    a.gn = wp.gn;
+    a.gk = wp.gk;
+    if (wp.gk > 1) {
+      a.ws_count = (unsigned*)workspace;
+      a.ws_tiles = (f4*)((uint8_t*)workspace + kSplitCounterBytes);
+    }
     a.x_stride = wp.x_stride;
     a.x_region = wp.x_region;
     a.x_phase = 0;
@@ -1347,6 +1435,39 @@ int ams_linear_grouped(const void* W_packed, const uint16_t* scales, int64_t sca
     case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
   }
   return AMS_ERR_FORMAT;
+}
+
+int ams_linear_workspace_bytes(int fmt, int M, int64_t N, int64_t K, size_t* bytes) {
+  if (!bytes) return AMS_ERR_NULL;
+  if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
+  int rec_k = 128, rec_bytes = 4096, f = FMT_FP16;  // fmt < 0: the fp16 baseline
+  if (fmt >= 0) {
+    const ams::FormatInfo* fi = ams::format_info(fmt);
+    if (!fi) return AMS_ERR_FORMAT;
+    rec_k = fi->rec_k, rec_bytes = fi->rec_bytes, f = fmt;
+  }
+  const int64_t n_strips = (N + 15) / 16;
+  const int n_rec = (int)((K + rec_k - 1) / rec_k);
+  *bytes = split_workspace_bytes(M, n_strips, choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes));
+  return AMS_OK;
+}
+
+int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K,
+                  int fmt, void* workspace, size_t workspace_bytes, void* stream) {
+  switch (fmt) {
+    case FMT_FP533: return run_linear<FMT_FP533>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP425: return run_linear<FMT_FP425>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP45: return run_linear<FMT_FP45>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+  }
+  return AMS_ERR_FORMAT;
+}
+
+int ams_fp16_linear_ws(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  return run_linear<FMT_FP16>(W, nullptr, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
 }
 
 int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* stream) {

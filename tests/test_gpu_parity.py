@@ -232,6 +232,52 @@ def test_fp16_baseline_matches_oracle(N, K, Ms):
         check_linear(y, O.fp16_linear(W, X), f"fp16 N={N} K={K} M={M}")
 
 
+# ---- K split over workgroups through a workspace -------------------------------------------------
+@pytest.mark.parametrize("fmt,ofmt", PAPER_PAIRS + [(ams.FP433, O.FP433)])
+def test_linear_with_workspace_matches_oracle(fmt, ofmt):
+    # one workspace, zero-filled once, reused by every call below: each call must leave it clean
+    ws = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+    split_seen = 0
+    for N, K, Ms in [(2560, 9728, (1, 8)), (5000, 4100, (1, 16)), (4096, 14336, (8,)), (5120, 25600, (1,))]:
+        W = synth.gaussian_weights(N, K, 95)
+        packed, scales = ams.ams_pack(fmt, W)
+        wp, sc = dev(packed), dev(scales)
+        rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(3, N, 97)])
+        codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+        for M in Ms:
+            need = ams.ams_linear_workspace_bytes(fmt, M, N, K)
+            assert need <= ws.numel()
+            split_seen += need > 0
+            X = synth.activations(M, K, 96 + M)
+            x = dev(X)
+            y1 = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws))
+            y2 = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws))  # the counters were left at zero
+            assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))  # deterministic whoever arrives last
+            assert np.all(np.isfinite(y1.astype(np.float64)))
+            check_linear(y1[:, rows], O.linear(codes, o_scales, X, ofmt), f"workspace N={N} K={K} M={M}")
+            # no workspace, or one that is too small: the plain path, bit for bit
+            y0 = host16(ams.ams_linear(wp, sc, x, N, fmt))
+            assert np.array_equal(host16(ams.ams_linear_ws(wp, sc, x, N, fmt, None)).view(np.uint16), y0.view(np.uint16))
+            assert np.array_equal(host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws[:256])).view(np.uint16), y0.view(np.uint16))
+    assert split_seen >= 3  # the cases above are meant to take the split path
+    torch.cuda.synchronize()
+    # partial tiles stay behind in the workspace; only the counters must be back at zero
+    assert not ws[: 4 * 16384].any()
+
+
+def test_fp16_baseline_with_workspace_matches_oracle():
+    ws = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+    for N, K, M in [(6144, 4096, 1), (5000, 4104, 8), (2560, 9728, 4)]:
+        assert 0 < ams.ams_linear_workspace_bytes(-1, M, N, K) <= ws.numel()
+        W = synth.gaussian_weights(N, K, 97)
+        X = synth.activations(M, K, 98)
+        y = host16(ams.ams_fp16_linear_ws(dev(W), dev(X), ws))
+        rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(3, N, 97)])
+        check_linear(y[:, rows], O.fp16_linear(W[rows], X), f"fp16 workspace N={N} K={K} M={M}")
+    torch.cuda.synchronize()
+    assert not ws[: 4 * 16384].any()
+
+
 def test_device_entry_points_reject_bad_arguments():
     lib = ams.load_library()
     W = synth.gaussian_weights(16, 96, 1)

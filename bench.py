@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
     ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all six formats (the step keeps the paper's two)")
     ap.add_argument("--group-scales", action="store_true", help="also time ams_linear_grouped (one scale per record-sized run of K) per layer")
+    ap.add_argument("--workspace", action="store_true", help="call ams_linear_ws / ams_fp16_linear_ws with a workspace (K may be split over workgroups)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
                    
@@ -215,6 +216,16 @@ def main():
         del W
     print(f"# setup {time.perf_counter() - t_setup:.1f}s, {n_copies} packed copies, {fp16_copies} fp16 copies per layer", file=sys.stderr)
 
+    ws = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda") if args.workspace else None
+
+    def linear(packed, scales, x, N, fmt, out):
+        if ws is None:
+            return ams.ams_linear(packed, scales, x, N, fmt, out=out)
+        return ams.ams_linear_ws(packed, scales, x, N, fmt, ws, out=out)
+
+    def fp16_linear(w, x, out):
+        return ams.ams_fp16_linear(w, x, out=out) if ws is None else ams.ams_fp16_linear_ws(w, x, ws, out=out)
+
     M = 1
     xs = {l.name: to_dev(synth.activations(M, l.K, 7), torch) for l in layers}
     ys = {l.name: torch.empty((M, l.N), dtype=torch.float16, device="cuda") for l in layers}
@@ -222,7 +233,7 @@ def main():
     def step(i):
         for l in layers:
             for fmt in fmts:
-                ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name])
+                linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name])
 
     # ---- the contract's timed region: W warm-up steps, K timed steps, sync on both sides.
     # One HIP graph per rotating copy holds the eight launches of a step; a step is one graph replay.
@@ -250,11 +261,11 @@ def main():
     per_layer = []
     n_launch = 8 * n_copies
     for l in layers:
-        t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % fp16_copies], xs[l.name], out=ys[l.name]), n_launch)
+        t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % fp16_copies], xs[l.name], ys[l.name]), n_launch)
         tlib = time_launches(torch, lambda i: torch.matmul(xs[l.name], l.w16[i % fp16_copies].t(), out=ys[l.name]), n_launch)
         for fmt in all_fmts:
-            t, pct = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch, replays=10, spread=True)
-            warm = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, out=ys[l.name]), n_launch)
+            t, pct = time_launches(torch, lambda i: linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name]), n_launch, replays=10, spread=True)
+            warm = time_launches(torch, lambda i: linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name]), n_launch)
             # second denominator: a bare read of the same packed bytes (same rotation), nothing computed
             t_read = time_launches(torch, lambda i: ams.ams_read_probe(l.packed[fmt][i % n_copies]), n_launch)
             t_grouped = None
@@ -287,7 +298,7 @@ def main():
     dl = next(l for l in layers if l.name == dom["layer"])
     dfmt = next(f for f, n in FMT_NAMES.items() if n == dom["fmt"])
     alg_bytes = dl.canon[dfmt] + 2 * dl.N + 2 * M * dl.K + 2 * M * dl.N
-    t_dom = time_launches(torch, lambda i: ams.ams_linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, out=ys[dl.name]), n_launch, replays=20)
+    t_dom = time_launches(torch, lambda i: linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
     roofline = {
         "bound": "hbm", "kernel": f"sweep_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
@@ -306,10 +317,10 @@ def main():
             for Mb in (1, 2, 4, 8, 16, 32):
                 x = to_dev(synth.activations(Mb, l.K, 9), torch)
                 y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
-                t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % fp16_copies], x, out=y), n_launch)
+                t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % fp16_copies], x, y), n_launch)
                 tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % fp16_copies].t(), out=y), n_launch)
                 for fmt in all_fmts:
-                    t = time_launches(torch, lambda i: ams.ams_linear(l.packed[fmt][i % n_copies], l.scales[fmt], x, l.N, fmt, out=y), n_launch)
+                    t = time_launches(torch, lambda i: linear(l.packed[fmt][i % n_copies], l.scales[fmt], x, l.N, fmt, y), n_launch)
                     sweep.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
                                   "GBps": round(l.canon[fmt] / t / 1e3, 1), "fp16_us": round(t16, 3),
                                   "library_gemm_fp16_us": round(tlib, 3), "speedup_vs_fp16": round(t16 / t, 3),
@@ -329,7 +340,7 @@ def main():
             if args.layers == "8b" else f"{args.layers} layer set, M=1, both formats",
             "linears_per_step": len(layers) * len(fmts), "packed_bytes_per_step": step_bytes,
             "hbm_peak_GBps": HBM_PEAK_GBPS, "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
-            "launch_floor_us": round(launch_floor, 3),
+            "launch_floor_us": round(launch_floor, 3), "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
         },
         "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",

@@ -947,23 +947,31 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
       // counts itself in; the one that arrives last adds all gk tiles in slice order (so the
       // result does not depend on who was last), finishes the strip and clears the counter
       // for the next call.  Nobody waits for anybody.
-      f4* wt = a.ws_tiles + ((size_t)gk * a.n_strips + strip) * MT * 64 + lane;
+      // The tiles travel as device-scope relaxed atomic stores and loads (they go to the level
+      // of the memory system all compute units share) and the count is taken only after the
+      // stores have been acknowledged; a device-scope fence would instead write back and
+      // invalidate the whole L2, which costs more than the Linear itself.
+      float* wt = (float*)(a.ws_tiles + ((size_t)gk * a.n_strips + strip) * MT * 64 + lane);
 #pragma unroll
-      for (int t = 0; t < MT; t++) wt[t * 64] = sum[t];
-      __threadfence();  // the tile is visible device-wide before the count
+      for (int t = 0; t < MT; t++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) __hip_atomic_store(wt + t * 256 + r, sum[t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // waits for the stores above
       unsigned before = 0;
-      if (lane == 0) before = atomicAdd(a.ws_count + strip, 1u);
+      if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       before = __builtin_amdgcn_readfirstlane(before);
       if (before != (unsigned)a.gk - 1) continue;
-      __threadfence();  // the others' tiles are visible before they are read
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the loads below stay behind the count
 #pragma unroll
       for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
       for (int q = 0; q < a.gk; q++) {
-        const f4* rt = a.ws_tiles + ((size_t)q * a.n_strips + strip) * MT * 64 + lane;
+        const float* rt = (const float*)(a.ws_tiles + ((size_t)q * a.n_strips + strip) * MT * 64 + lane);
 #pragma unroll
-        for (int t = 0; t < MT; t++) sum[t] += rt[t * 64];
+        for (int t = 0; t < MT; t++)
+#pragma unroll
+          for (int r = 0; r < 4; r++) sum[t][r] += __hip_atomic_load(rt + t * 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      if (lane == 0) a.ws_count[strip] = 0;
+      if (lane == 0) __hip_atomic_store(a.ws_count + strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     f4 sc;
     if constexpr (GS)
@@ -1206,8 +1214,11 @@ size_t split_workspace_bytes(int M, int64_t n_strips, int gk) {
 // against 5 strips x a quarter of K on 256) and when the batch is large (every workgroup
 // stages the activations of its own slice of K only).  The estimate is bytes a workgroup
 // moves: its weight records, half weight for the activations it stages (they come from
-// L2), and a fixed charge for the exchange through the workspace.
+// L2), and a fixed charge for the exchange through the workspace (fitted to measurements on
+// the Llama and Qwen shapes: below a batch of 4 the stream is bound by the memory system as a
+// whole and a split never paid).
 int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec_bytes) {
+  if (M < 4) return 1;
   int best = 1;
   double best_cost = 0;
   for (int gk = 1; gk <= 8; gk *= 2) {
@@ -1217,7 +1228,7 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
     const double slice = (double)((n_rec + gk - 1) / gk);
     const double n_phase = std::max(1.0, slice / p.rc);
     double cost = p.spw * slice * rec_bytes + 0.5 * M * slice * rec_k * 2 + 8192.0 * (n_phase - 1);
-    if (gk > 1) cost += 24576.0 + 2048.0 * gk * p.spw * (M > 16 ? 2 : 1);
+    if (gk > 1) cost += 49152.0 + 2048.0 * gk * p.spw * (M > 16 ? 2 : 1);
     if (best_cost == 0 || cost < best_cost) best = gk, best_cost = cost;
   }
   return best;

@@ -157,6 +157,7 @@ struct LinearArgs {
   // split of K over gk workgroups per strip (sweep kernel with a workspace): workgroups along N,
   // slices of K, per-slice partial tiles [gk][strip][MT][64] f4, per-strip arrival counters
   int gn, gk;
+  int wps;  // sweep kernel: wavefronts that share a strip (the workgroup works on S / wps strips at a time)
   f4* ws_tiles;
   unsigned* ws_count;
 };
@@ -765,12 +766,12 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
 // order, scaled, converted, stored.  The activations are staged once per workgroup in LDS
 // in operand order; when M x K does not fit, K is walked in phases of rc records per strip
 // and the parked tiles accumulate over the phases.  The grid is one resident round.
-template <int FMT, int MT, int LR, bool NT, bool GS = false>
+template <int FMT, int MT, int LR, bool NT, bool GS = false, bool GROUPS = false>
 __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K;
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
-               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk));
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wps));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = nthr >> 6;
@@ -786,14 +787,27 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   const bool one_phase = RC >= rec_hi - rec_lo;
   const int mc = min(a.M, 16);  // activation rows of an MFMA tile that exist
   _Float16* xs = (_Float16*)smem;
-  f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][S][MT][4 K-quarters][mc]
+  f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][wps][MT][4 K-quarters][mc]
+  // The waves come in S / wps groups of wps; group vs owns the local strips vs, vs + sg, ...
+  // and deals their records to its waves one by one (wps = S: all waves on one strip at a
+  // time; fewer when the parked tiles, one per strip and wave of its group, must be fewer).
+  // (GROUPS = false is the common case wps = S, spelled out so that it costs nothing.)
+  const int wps = GROUPS ? a.wps : S;
+  const int sg = GROUPS ? S / wps : 1;
+  const int vs = GROUPS ? (int)((unsigned)wave / (unsigned)wps) : 0, vw = wave - vs * wps;
+  const int ns_v = vs < ns ? (ns - vs + sg - 1) / sg : 0;  // strips of this wave's group
+  // the group's j-th strip is local strip vs + j * sg = strip strip0 + j * strip_step of the
+  // matrix; a group without strips reads (only reads) the workgroup's first strip
+  const int strip0 = g + (ns_v > 0 ? vs : 0) * G, strip_step = (ns_v > 0 ? sg : 0) * G;
   const int m_lo = lane & 15, kq = lane >> 4;
   const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
   // lanes whose activation row does not exist read row 0: they only feed output columns never stored
   const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
   const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
   const int part_f4 = MT * 4 * mc;  // f4 per parked tile
-  f4* const my_part = parts + (size_t)wave * part_f4 + kq * mc + m_lo;  // this wave's tile of local strip 0
+  // this wave's tile of its group's first strip; the next strips' tiles follow part_step apart
+  f4* const my_part = parts + (size_t)((ns_v > 0 ? vs : 0) * wps + vw) * part_f4 + kq * mc + m_lo;
+  const int part_step = sg * wps * part_f4;
 
   const bool vec_x = (a.K & 7) == 0;
   const int total_units = a.M << a.x_shift;
@@ -809,8 +823,8 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
   for (int rec_base = rec_lo; rec_base < rec_hi; rec_base += RC) {
     const int n_rec = min(RC, rec_hi - rec_base);                 // records per strip in this phase
-    const int total = ns * n_rec;                                 // records of this workgroup
-    const int cnt = wave < total ? (total - wave + S - 1) / S : 0;  // records of this wave
+    const int total = ns_v * n_rec;                                  // records of this wave's group
+    const int cnt = vw < total ? (total - vw + wps - 1) / wps : 0;  // records of this wave
     if (rec_base > rec_lo) __syncthreads();  // everyone is done with the previous phase's activations
     const int k0 = rec_base * REC_K;
 
@@ -831,9 +845,10 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
 
     // Head of the weight stream.  The prefetch cursor (position in the list, local strip,
     // record) stops at the wave's last record; a wave without records reads record 0.
-    int pf = wave < total ? wave : 0, pj = 0, pr = pf;
+    int pf = vw < total ? vw : 0, pj = 0, pr = pf;
     while (pr >= n_rec) pr -= n_rec, pj++;
-    int cj = pj, cr = pr;  // local strip and record (inside the phase) of the record being multiplied
+    int cj = pj, cr = pr;  // strip (counted inside the group) and record (inside the phase) being multiplied
+
     // LR records are in flight while a record is being restored: the ring has one slot more,
     // and a step first requests the record LR places ahead into the slot freed by the step
     // before, then works on its own (a refill into the slot being read would have to wait
@@ -845,11 +860,12 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     };
     Slot ring[RS];
     auto request = [&](Slot& slot) {
-      load_rec<FMT, NT>(slot.r, a, g + pj * G, rec_base + pr, lane);
+      const int strip = strip0 + pj * strip_step;
+      load_rec<FMT, NT>(slot.r, a, strip, rec_base + pr, lane);
       if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
-        slot.gs = *(const us4*)(a.scales + ((size_t)(g + pj * G) * a.n_sg + ((rec_base + pr) >> a.sg_shift)) * 16 + 4 * kq);
-      if (pf + S < total) {
-        pf += S, pr += S;
+        slot.gs = *(const us4*)(a.scales + ((size_t)strip * a.n_sg + ((rec_base + pr) >> a.sg_shift)) * 16 + 4 * kq);
+      if (pf + wps < total) {
+        pf += wps, pr += wps;
         while (pr >= n_rec) pr -= n_rec, pj++;
       }
     };
@@ -862,7 +878,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     // while those are in flight: every tile slot cleared (a wave need not meet every strip when a
     // strip has fewer records than the workgroup has waves)
     if (rec_base == rec_lo)
-      for (int i = tid; i < ns * S * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
+      for (int i = tid; i < ns * wps * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
     if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
     __syncthreads();
 
@@ -873,7 +889,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
 
     auto park = [&]() {
       if (m_lo < mc) {
-        f4* t = my_part + (size_t)cj * S * part_f4;
+        f4* t = my_part + cj * part_step;
         if (one_phase) {
 #pragma unroll
           for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
@@ -904,7 +920,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
         mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc);
       }
       pending = true;
-      cr += S;
+      cr += wps;
       if (cr >= n_rec) {
         park();
         pending = false;
@@ -928,15 +944,15 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     if (pending) park();
   }
 
-  // Finish the strips, one per wave: the S parked tiles added in wave order.
+  // Finish the strips, one per wave: the wps parked tiles added in wave order.
   __syncthreads();
   for (int j = wave; j < ns; j += S) {
     f4 sum[MT];
 #pragma unroll
     for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
     if (m_lo < mc) {
-      const f4* t0 = parts + (size_t)j * S * part_f4 + kq * mc + m_lo;
-      for (int w = 0; w < S; w++) {
+      const f4* t0 = parts + (size_t)j * wps * part_f4 + kq * mc + m_lo;
+      for (int w = 0; w < wps; w++) {
 #pragma unroll
         for (int t = 0; t < MT; t++) sum[t] += t0[(size_t)w * part_f4 + t * 4 * mc];
       }
@@ -1152,7 +1168,7 @@ StreamPlan make_stream_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec
 
 struct SweepPlan {
   bool ok;
-  int S, lr, spw, grid, gn, gk, rc, x_shift, x_stride, x_region;
+  int S, lr, spw, grid, gn, gk, wps, rc, x_shift, x_stride, x_region;
   size_t lds;
 };
 
@@ -1173,13 +1189,18 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
   const int wg_along_n = kNumCU / gk;
   p.spw = (int)((n_strips + wg_along_n - 1) / wg_along_n);
   const size_t tile_bytes = (size_t)mt * 4 * mc * 16;  // one parked tile
-  if (any_shape) p.spw = (int)std::max<int64_t>(1, std::min<int64_t>(p.spw, (64 * 1024) / (16 * tile_bytes)));
+  if (any_shape) p.spw = (int)std::max<int64_t>(1, std::min<int64_t>(p.spw, (48 * 1024) / tile_bytes));
   p.gn = (int)((n_strips + p.spw - 1) / p.spw);
   p.grid = p.gn * gk;
   p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * (n_rec_all / gk));  // n_rec_all / gk: the shortest slice
   if (p.S < 1) return p;
   p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
-  const size_t parts = (size_t)p.spw * p.S * tile_bytes;
+  // waves per strip: all of them unless the parked tiles (one per strip and wave of its group)
+  // would take more than 48 KB; never fewer than leaves every group of waves a strip
+  p.wps = p.S;
+  if (p.S == 16)
+    while (p.wps > 1 && (size_t)p.spw * p.wps * tile_bytes > 48 * 1024 && 16 / (p.wps / 2) <= p.spw) p.wps /= 2;
+  const size_t parts = (size_t)p.spw * p.wps * tile_bytes;
   for (int n_phase = 1; n_phase <= (any_shape ? n_rec : 8) && n_phase <= n_rec; n_phase++) {
     const int rc = (n_rec + n_phase - 1) / n_phase;
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
@@ -1224,11 +1245,18 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
   for (int gk = 1; gk <= 8; gk *= 2) {
     if (gk > 1 && (n_rec / gk < 8 || n_strips > kSplitMaxStrips)) break;
     const SweepPlan p = make_sweep_plan(fmt, M, n_strips, n_rec, rec_k, false, gk);
-    if (!p.ok) continue;
+    int spw = p.spw, rc = p.rc;
+    if (!p.ok) {
+      if (gk > 1) continue;
+      // without a split the shape would go to the contiguous-piece kernel: price that one
+      const StreamPlan sp = make_stream_plan(fmt, M, n_strips, n_rec, rec_k);
+      if (!sp.ok) continue;
+      spw = sp.spw, rc = sp.rc;
+    }
     const double slice = (double)((n_rec + gk - 1) / gk);
-    const double n_phase = std::max(1.0, slice / p.rc);
-    double cost = p.spw * slice * rec_bytes + 0.5 * M * slice * rec_k * 2 + 8192.0 * (n_phase - 1);
-    if (gk > 1) cost += 49152.0 + 2048.0 * gk * p.spw * (M > 16 ? 2 : 1);
+    const double n_phase = std::max(1.0, slice / rc);
+    double cost = spw * slice * rec_bytes + 0.5 * M * slice * rec_k * 2 + 8192.0 * (n_phase - 1);
+    if (gk > 1) cost += 49152.0 + 2048.0 * gk * spw * (M > 16 ? 2 : 1);
     if (best_cost == 0 || cost < best_cost) best = gk, best_cost = cost;
   }
   return best;
@@ -1264,14 +1292,20 @@ enum KernelKind { kSweep, kSweepCached, kSweepGrouped, kStream, kPhase };
 
 template <int FMT, int MT>
 int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  const bool groups = a.wps != S;  // wave groups per strip: their own instantiation, the common case stays lean
   if (kind == kSweepGrouped) {
-    if constexpr (FMT != FMT_FP16) return launch(sweep_kernel<FMT, MT, 2, true, true>, a, grid, S, lds, st);
+    if constexpr (FMT != FMT_FP16)
+      return groups ? launch(sweep_kernel<FMT, MT, 2, true, true, true>, a, grid, S, lds, st)
+                    : launch(sweep_kernel<FMT, MT, 2, true, true, false>, a, grid, S, lds, st);
   } else if (kind == kSweep || kind == kSweepCached) {
     if constexpr (FMT == FMT_FP16) {
-      if (lr == 1) return launch(sweep_kernel<FMT, MT, 1, false>, a, grid, S, lds, st);
-    } else {
-      if (lr == 2) return kind == kSweep ? launch(sweep_kernel<FMT, MT, 2, true>, a, grid, S, lds, st)
-                                         : launch(sweep_kernel<FMT, MT, 2, false>, a, grid, S, lds, st);
+      if (lr == 1)
+        return groups ? launch(sweep_kernel<FMT, MT, 1, false, false, true>, a, grid, S, lds, st)
+                      : launch(sweep_kernel<FMT, MT, 1, false, false, false>, a, grid, S, lds, st);
+    } else if (lr == 2) {
+      if (groups) return launch(sweep_kernel<FMT, MT, 2, true, false, true>, a, grid, S, lds, st);
+      return kind == kSweep ? launch(sweep_kernel<FMT, MT, 2, true>, a, grid, S, lds, st)
+                            : launch(sweep_kernel<FMT, MT, 2, false>, a, grid, S, lds, st);
     }
   } else if (kind == kStream) {
     switch (lr) {
@@ -1320,6 +1354,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   }
   a.gn = 1;
   a.gk = 1;
+  a.wps = 1;
   a.ws_tiles = nullptr;
   a.ws_count = nullptr;
   constexpr int REC_BYTES = FMT == FMT_FP16 ? 4096 : Fmt<FMT>::REC_BYTES;
@@ -1334,6 +1369,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   if (wp.ok) {
     a.gn = wp.gn;
     a.gk = wp.gk;
+    a.wps = wp.wps;
     if (wp.gk > 1) {
       a.ws_count = (unsigned*)workspace;
       a.ws_tiles = (f4*)((uint8_t*)workspace + kSplitCounterBytes);

@@ -11,7 +11,8 @@
 // stream_kernel (equal contiguous record pieces per wavefront; for shapes whose parked
 // tiles would not fit the sweep's LDS) and phase_kernel (one workgroup per strip,
 // activations staged per wavefront in phases; the last fallback).
-// Partial tiles are combined through LDS: no global workspace, no atomics.
+// Partial tiles are combined through LDS, deterministically; only the entry points that take
+// a workspace also split K over workgroups and exchange fp32 tiles through it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -33,7 +33,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
 # by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77689 + 56) * 1024}
+MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77697 + 56) * 1024}
 FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2", 2: "fp4.5-e2m2", 3: "fp4.33-e2m2", 4: "fp6-e2m3", 5: "fp5-e2m2"}
 
 

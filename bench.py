@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
 # by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77697 + 56) * 1024}
-FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2", 2: "fp4.5-e2m2", 3: "fp4.33-e2m2", 4: "fp6-e2m3", 5: "fp5-e2m2"}
+FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2", 2: "fp4.5-e2m2", 3: "fp4.33-e2m2", 4: "fp6-e2m3", 5: "fp5-e2m2", 6: "fp4-e2m1"}
 
 
 def parse_args():
@@ -171,7 +171,7 @@ def profile_kernel(args, shapes, torch, ams, synth):
         ws = [to_dev(W, torch) for _ in range(3)]
         run = lambda i: ams.ams_fp16_linear(ws[i % 3], x, out=y)
     else:
-        fmt = {"fp5.33": ams.FP533, "fp4.25": ams.FP425, "fp4.5": ams.FP45, "fp4.33": ams.FP433, "fp6": ams.FP6, "fp5": ams.FP5}[fmt_s]
+        fmt = {"fp5.33": ams.FP533, "fp4.25": ams.FP425, "fp4.5": ams.FP45, "fp4.33": ams.FP433, "fp6": ams.FP6, "fp5": ams.FP5, "fp4": ams.FP4}[fmt_s]
         p, s = ams.ams_pack(fmt, W)
         ps = [to_dev(p, torch) for _ in range(n_copies)]
         sc = to_dev(s, torch)
@@ -208,7 +208,7 @@ def main():
     n_copies = max(2, -(-args.copies_mb * (1 << 20) // set_bytes))
     fp16_copies = max(2, -(-args.copies_mb * (1 << 20) // (3 * set_bytes)))
     fmts = (ams.FP533, ams.FP425)  # the step: the two formats the paper builds kernels for
-    all_fmts = (ams.FP6, ams.FP533, ams.FP5, ams.FP45, ams.FP433, ams.FP425) if args.all_formats else fmts
+    all_fmts = (ams.FP6, ams.FP533, ams.FP5, ams.FP45, ams.FP433, ams.FP425, ams.FP4) if args.all_formats else fmts
     layers = []
     for i, (name, (N, K)) in enumerate(shapes.items()):
         W = maker(N, K, 100 + i)

@@ -16,7 +16,7 @@
  *   - fp16 values travel as uint16_t bit patterns (IEEE binary16).
  *   - W is [N, K]: N output channels (rows), K input channels; one fp16 scale per row.
  *   - A "code" is one weight's mini-float [S | E(2) | M(m)] with exponent bias 1,
- *     subnormals, and no inf/NaN (Sec. 2.2, Table 1): 6 bits for e2m3, 5 for e2m2.
+ *     subnormals, and no inf/NaN (Sec. 2.2, Table 1): 6 bits for e2m3, 5 for e2m2, 4 for e2m1.
  */
 #ifndef AMS_H_
 #define AMS_H_
@@ -39,7 +39,8 @@ enum {
   AMS_FMT_FP45_E2M2 = 2,  /* e2m2 codes, groups of 2 share it: 4.5 bits per weight */
   AMS_FMT_FP433_E2M2 = 3, /* e2m2 codes, groups of 3 share it: 13/3 bits per weight */
   AMS_FMT_FP6_E2M3 = 4,   /* plain e2m3: 6 bits per weight */
-  AMS_FMT_FP5_E2M2 = 5    /* plain e2m2: 5 bits per weight */
+  AMS_FMT_FP5_E2M2 = 5,   /* plain e2m2: 5 bits per weight */
+  AMS_FMT_FP4_E2M1 = 6    /* plain e2m1: 4 bits per weight */
 };
 
 enum {
@@ -66,7 +67,7 @@ int ams_code_bits(int fmt);
  * Size in bytes of the packed weight buffer in this library's gfx950 layout
  * (what ams_pack writes and ams_dequant / ams_linear read).  The layout is opaque:
  * records of 16 rows x 96 weights (FP5.33, FP4.33, FP6) or 16 rows x 128 weights
- * (FP4.25, FP4.5, FP5), so N is padded to a multiple of 16 and K to a multiple of
+ * (FP4.25, FP4.5, FP5, FP4), so N is padded to a multiple of 16 and K to a multiple of
  * 96 / 128; padding holds zero codes.  Without padding the size is exactly
  * N * K * bits-per-weight / 8.
  */
@@ -76,7 +77,7 @@ int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
  * Size in bytes of the paper's own packing: one uint16 per 3 weights for FP5.33
  * (Sec. 3.3 item 1), 17 uint16 per 64 weights for FP4.25 (Sec. 3.2); for the other
  * formats the densest whole-byte packing per row (9 bytes per 16 weights, 13 per 24,
- * 3 per 4, 5 per 8).  This is the "algorithmic" byte count used when bandwidth is
+ * 3 per 4, 5 per 8, 1 per 2).  This is the "algorithmic" byte count used when bandwidth is
  * reported.
  */
 int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);

@@ -19,6 +19,7 @@ FP45 = 2  # AMS_FMT_FP45_E2M2
 FP433 = 3  # AMS_FMT_FP433_E2M2
 FP6 = 4  # AMS_FMT_FP6_E2M3
 FP5 = 5  # AMS_FMT_FP5_E2M2
+FP4 = 6  # AMS_FMT_FP4_E2M1
 SEARCH_SET_BIT = 0  # AMS_SEARCH_SET_BIT
 SEARCH_REROUND = 1  # AMS_SEARCH_REROUND
 MAX_M = 32

@@ -151,7 +151,9 @@ inline int mag_pos(int fmt, int i) { return is_e2m3(fmt) ? 8 - 4 * i : 9 - 3 * i
 // Writes the records of one strip.  codes: 16 rows of K bytes (row pointer NULL = padding row).
 void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], int64_t K, uint8_t* strip_out) {
   const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
-  const int mag_bits = fi.code_bits - 2;  // bits of a remainder without its sign
+  // FP4-e2m1 has no last bit beside its remainder: the nibble is the whole code
+  const bool whole = fmt == ams::kFmtFp4;
+  const int mag_bits = whole ? fi.code_bits - 1 : fi.code_bits - 2;  // bits of a remainder without its sign
   for (int64_t j = 0; j < n_rec; j++) {
     uint8_t* rec = strip_out + j * fi.rec_bytes;
     for (int l = 0; l < ams::kLanes; l++) {
@@ -162,7 +164,7 @@ void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], in
       for (int q = 0; q < fi.lane_k; q++) {
         const int c = (row && kbase + q < K) ? row[kbase + q] : 0;  // padding is code 0
         const ams::Place p = ams::place(fmt, q);
-        const uint32_t rem = (uint32_t)c >> 1, lsb = (uint32_t)c & 1;
+        const uint32_t rem = whole ? (uint32_t)c : (uint32_t)c >> 1, lsb = whole ? 0u : (uint32_t)c & 1;
         uint32_t hw = (rem >> mag_bits) << sign_pos(fmt, p.i) | (rem & ((1u << mag_bits) - 1)) << mag_pos(fmt, p.i);
         const int sb = ams::side_bit(fmt, q);
         if (sb >= 0)
@@ -179,7 +181,8 @@ void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], in
 
 void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* strip_in, int64_t K, uint8_t* const rows[16]) {
   const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
-  const int mag_bits = fi.code_bits - 2;
+  const bool whole = fmt == ams::kFmtFp4;
+  const int mag_bits = whole ? fi.code_bits - 1 : fi.code_bits - 2;
   for (int64_t j = 0; j < n_rec; j++) {
     const uint8_t* rec = strip_in + j * fi.rec_bytes;
     for (int l = 0; l < ams::kLanes; l++) {
@@ -197,7 +200,7 @@ void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* strip_in, int64_
         const uint32_t rem = ((hw >> sign_pos(fmt, p.i)) & 1) << mag_bits | ((hw >> mag_pos(fmt, p.i)) & ((1u << mag_bits) - 1));
         const int sb = ams::side_bit(fmt, q);
         const uint32_t lsb = sb >= 0 ? (side >> sb) & 1 : (hw >> 12) & 1;
-        row[kbase + q] = (uint8_t)(rem << 1 | lsb);
+        row[kbase + q] = whole ? (uint8_t)rem : (uint8_t)(rem << 1 | lsb);
       }
     }
   }
@@ -274,7 +277,8 @@ int ams_canonical_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
     case AMS_FMT_FP45_E2M2: *bytes = (size_t)9 * (size_t)((K + 15) / 16) * (size_t)N; break;    // 16 nibbles + 8 shared bits
     case AMS_FMT_FP433_E2M2: *bytes = (size_t)13 * (size_t)((K + 23) / 24) * (size_t)N; break;  // 24 nibbles + 8 shared bits
     case AMS_FMT_FP6_E2M3: *bytes = (size_t)3 * (size_t)((K + 3) / 4) * (size_t)N; break;       // 4 codes of 6 bits
-    default: *bytes = (size_t)5 * (size_t)((K + 7) / 8) * (size_t)N; break;                     // FP5: 8 codes of 5 bits
+    case AMS_FMT_FP5_E2M2: *bytes = (size_t)5 * (size_t)((K + 7) / 8) * (size_t)N; break;       // 8 codes of 5 bits
+    default: *bytes = (size_t)((K + 1) / 2) * (size_t)N; break;                                 // FP4: 2 codes per byte
   }
   return AMS_OK;
 }

@@ -37,9 +37,10 @@ constexpr int FMT_FP45 = AMS_FMT_FP45_E2M2;
 constexpr int FMT_FP433 = AMS_FMT_FP433_E2M2;
 constexpr int FMT_FP6 = AMS_FMT_FP6_E2M3;
 constexpr int FMT_FP5 = AMS_FMT_FP5_E2M2;
+constexpr int FMT_FP4 = AMS_FMT_FP4_E2M1;
 constexpr int FMT_FP16 = 100;  // internal: unquantized row-major fp16 weights (baseline)
 static_assert(FMT_FP533 == ams::kFmtFp533 && FMT_FP425 == ams::kFmtFp425 && FMT_FP45 == ams::kFmtFp45 &&
-              FMT_FP433 == ams::kFmtFp433 && FMT_FP6 == ams::kFmtFp6 && FMT_FP5 == ams::kFmtFp5, "format numbers");
+              FMT_FP433 == ams::kFmtFp433 && FMT_FP6 == ams::kFmtFp6 && FMT_FP5 == ams::kFmtFp5 && FMT_FP4 == ams::kFmtFp4, "format numbers");
 
 constexpr float kTwo14 = 16384.0f;  // restored patterns are value * 2^-14
 
@@ -202,6 +203,11 @@ __device__ __forceinline__ void restore_rec(const LaneRec<FMT>& r, uint32_t (&o)
     const uint32_t spread = spread_side_byte((uint32_t)r.t);
 #pragma unroll
     for (int d = 0; d < 4; d++) restore_fp425(r.w[d], pair_bits_e2m2(spread, d), &o[4 * d]);
+  } else if constexpr (FMT == FMT_FP4) {
+    // an e2m1 code is an e2m2 remainder whose last bit is 0
+    const uint32_t none[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int d = 0; d < 4; d++) restore_e2m2(r.w[d], none, &o[4 * d]);
   } else {
     // FP4.33: one side byte for all words; FP4.5: one per two words; FP5: one per word
     constexpr int WORDS_PER_BYTE = FMT == FMT_FP433 ? 3 : (FMT == FMT_FP45 ? 2 : 1);
@@ -1453,7 +1459,8 @@ int ams_dequant_grouped(int fmt, const void* W_packed, const uint16_t* scales, i
     case FMT_FP45: go(dequant_kernel<FMT_FP45>); break;
     case FMT_FP433: go(dequant_kernel<FMT_FP433>); break;
     case FMT_FP6: go(dequant_kernel<FMT_FP6>); break;
-    default: go(dequant_kernel<FMT_FP5>); break;
+    case FMT_FP5: go(dequant_kernel<FMT_FP5>); break;
+    default: go(dequant_kernel<FMT_FP4>); break;
   }
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
@@ -1467,6 +1474,7 @@ int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, 
     case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream);
     case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream);
     case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream);
+    case FMT_FP4: return run_linear<FMT_FP4>(W_packed, scales, X, Y, M, N, K, stream);
   }
   return AMS_ERR_FORMAT;
 }
@@ -1481,6 +1489,7 @@ int ams_linear_grouped(const void* W_packed, const uint16_t* scales, int64_t sca
     case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
     case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
     case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
+    case FMT_FP4: return run_linear<FMT_FP4>(W_packed, scales, X, Y, M, N, K, stream, scale_group);
   }
   return AMS_ERR_FORMAT;
 }
@@ -1509,6 +1518,7 @@ int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* 
     case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
     case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
     case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
+    case FMT_FP4: return run_linear<FMT_FP4>(W_packed, scales, X, Y, M, N, K, stream, 0, workspace, workspace_bytes);
   }
   return AMS_ERR_FORMAT;
 }

@@ -36,6 +36,7 @@
 //   FP5    (k=1)  every weight its own bit;                 side byte d, bit 4h + i
 //   FP6    (k=1)  member 0: bit 12 of its half-word; members 1, 2: side 16 bits,
 //                 bit 8h + 2d + (i - 1)
+//   FP4    (e2m1) a nibble is the whole code: the e2m2 layout with every last bit 0
 // With the groups of FP4.5 / FP4.33 running across words, the last bits needed for the
 // four restored pairs of a word are the same for all words of the group.
 //
@@ -55,7 +56,7 @@ constexpr int kStripRows = 16;
 constexpr int kLanes = 64;
 
 // format numbers of the C ABI
-constexpr int kFmtFp533 = 0, kFmtFp425 = 1, kFmtFp45 = 2, kFmtFp433 = 3, kFmtFp6 = 4, kFmtFp5 = 5, kNumFormats = 6;
+constexpr int kFmtFp533 = 0, kFmtFp425 = 1, kFmtFp45 = 2, kFmtFp433 = 3, kFmtFp6 = 4, kFmtFp5 = 5, kFmtFp4 = 6, kNumFormats = 7;
 
 struct FormatInfo {
   int group;        // weights sharing one last mantissa bit
@@ -76,6 +77,7 @@ constexpr FormatInfo kFormats[kNumFormats] = {
     {3, 5, 96, 24, 12, 1, 832, 24, 7.0},    // FP4.33-e2m2
     {1, 6, 96, 24, 16, 2, 1152, 24, 7.5},   // FP6-e2m3
     {1, 5, 128, 32, 16, 4, 1280, 8, 7.0},   // FP5-e2m2
+    {1, 4, 128, 32, 16, 0, 1024, 8, 6.0},   // FP4-e2m1
 };
 
 inline const FormatInfo* format_info(int fmt) { return fmt >= 0 && fmt < kNumFormats ? &kFormats[fmt] : nullptr; }
@@ -92,7 +94,7 @@ constexpr Place place(int fmt, int j) {
     case kFmtFp6: return {j / 6, (j % 6) / 3, j % 3};
     case kFmtFp433: return {j % 3, (j / 3) / 4, (j / 3) % 4};
     case kFmtFp45: return {2 * (j / 16) + j % 2, ((j % 16) / 2) / 4, ((j % 16) / 2) % 4};
-    default: return {j / 8, (j % 8) / 4, j % 4};  // FP4.25, FP5
+    default: return {j / 8, (j % 8) / 4, j % 4};  // FP4.25, FP5, FP4
   }
 }
 
@@ -122,7 +124,7 @@ constexpr int side_bit(int fmt, int j) {
     case kFmtFp45: return 8 * (p.d / 2) + 4 * p.h + p.i;
     case kFmtFp5: return 8 * p.d + 4 * p.h + p.i;
     case kFmtFp6: return p.i == 0 ? -1 : 8 * p.h + 2 * p.d + (p.i - 1);
-    default: return -1;  // FP5.33: bit 12 of the half-word
+    default: return -1;  // FP5.33: bit 12 of the half-word; FP4: there is none
   }
 }
 

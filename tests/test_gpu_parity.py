@@ -13,7 +13,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]  # the two formats the paper builds kernels for
-PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2)]
+PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2), (ams.FP4, O.FP4_E2M1)]
 REL_L2_TOL = 1e-3
 MAX_ABS_TOL = 2e-2  # relative to rms(Y_ref)
 
@@ -113,7 +113,7 @@ def test_reround_packed_weights_through_the_kernels(fmt, ofmt):
     check_linear(y, O.linear(codes, o_scales, X, ofmt), "reround")
 
 
-REC_K = {ams.FP533: 96, ams.FP425: 128, ams.FP45: 128, ams.FP433: 96, ams.FP6: 96, ams.FP5: 128}
+REC_K = {ams.FP533: 96, ams.FP425: 128, ams.FP45: 128, ams.FP433: 96, ams.FP6: 96, ams.FP5: 128, ams.FP4: 128}
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)

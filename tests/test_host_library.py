@@ -15,8 +15,8 @@ from paper_2510_16045_amd import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]  # the two formats the paper builds kernels for
-PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2)]
-REC = {ams.FP533: (96, 1024), ams.FP425: (128, 1088), ams.FP45: (128, 1152), ams.FP433: (96, 832), ams.FP6: (96, 1152), ams.FP5: (128, 1280)}
+PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2), (ams.FP4, O.FP4_E2M1)]
+REC = {ams.FP533: (96, 1024), ams.FP425: (128, 1088), ams.FP45: (128, 1152), ams.FP433: (96, 832), ams.FP6: (96, 1152), ams.FP5: (128, 1280), ams.FP4: (128, 1024)}
 
 
 def test_library_exports_every_declared_symbol():
@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
     assert lib.ams_version() >= 100
     assert lib.ams_strerror(0) == b"ok"
-    assert [lib.ams_group_size(f) for f in range(8)] == [3, 4, 2, 3, 1, 1, 0, 0]
-    assert [lib.ams_code_bits(f) for f in range(8)] == [6, 5, 5, 5, 6, 5, 0, 0]
+    assert [lib.ams_group_size(f) for f in range(9)] == [3, 4, 2, 3, 1, 1, 1, 0, 0]
+    assert [lib.ams_code_bits(f) for f in range(9)] == [6, 5, 5, 5, 6, 5, 4, 0, 0]
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)

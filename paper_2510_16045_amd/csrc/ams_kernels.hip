@@ -5,12 +5,11 @@
 // Every lane loads its 16-byte chunk of a record with one dwordx4 (a record is one
 // contiguous 1 KiB access per wavefront), restores the fp16 pairs in registers and feeds
 // them as the A operand of v_mfma_f32_16x16x32_f16; the activations are staged in LDS in
-// the operand order the restoration produces.  Three kernels share these pieces:
+// the operand order the restoration produces.  Two kernels share these pieces:
 // sweep_kernel (the default: one resident round of workgroups, strips dealt round robin,
 // records dealt to the wavefronts one by one, so the grid reads one moving window),
 // stream_kernel (equal contiguous record pieces per wavefront; for shapes whose parked
-// tiles would not fit the sweep's LDS) and phase_kernel (one workgroup per strip,
-// activations staged per wavefront in phases; the last fallback).
+// tiles would not fit the sweep's LDS; it takes any shape).
 // Partial tiles are combined through LDS, deterministically; only the entry points that take
 // a workspace also split K over workgroups and exchange fp32 tiles through it.
 #include <hip/hip_runtime.h>
@@ -148,7 +147,6 @@ struct LinearArgs {
   int n_rec;     // records per strip
   int x_stride;  // halfs between activation rows inside a wave's LDS region
   int x_region;  // halfs of one wave's LDS region
-  int x_phase;   // records of activations a wave stages at a time (a multiple of the ring depth)
   int x_shift;   // log2 of the staging units per activation row, rounded up to a power of two
   int n_strips;  // strips of 16 output channels
   int spw;       // stream kernel: strips per workgroup
@@ -380,128 +378,6 @@ __device__ __forceinline__ void stage_x_unaligned(_Float16* xs, const LinearArgs
     const uint16_t v = k < a.K ? a.X[(size_t)m * a.K + k] : (uint16_t)0;
     const int rl = kk / Fmt<FMT>::REC_K, kr = kk - rl * Fmt<FMT>::REC_K;
     ((uint16_t*)xs)[m * a.x_stride + rl * Fmt<FMT>::REC_K + x_slot<FMT>(kr)] = v;
-  }
-}
-
-// Y[m, n] = fp16( s_n * sum_k value(code[n,k]) * X[m,k] ), one workgroup per strip of 16
-// output channels.  The S wavefronts of the workgroup take contiguous runs of the
-// strip's records.  Each wave keeps LR records in flight in a register ring whose
-// loads are unconditional (addresses clamped to the wave's last record) so that the
-// ring drains one record at a time; it stages the activations of its own K-range, XP
-// records at a time, in a private LDS region (no workgroup barrier inside the stream);
-// the partial 16x16 tiles are summed through LDS at the end.
-template <int FMT, int MT, int LR>
-__global__ void __launch_bounds__(1024) phase_kernel(LinearArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int REC_K = Fmt<FMT>::REC_K;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int S = blockDim.x >> 6;
-  const int strip = blockIdx.x;
-  const int r_begin = (int)((unsigned)(wave * a.n_rec) / (unsigned)S), r_end = (int)((unsigned)((wave + 1) * a.n_rec) / (unsigned)S);
-  const int r_last = r_end - 1;  // S <= n_rec, so every wave owns at least one record
-  _Float16* xs = (_Float16*)smem + (size_t)wave * a.x_region;
-  const int m_lo = lane & 15, kq = lane >> 4;
-  // lanes whose activation row does not exist read row 0: they only feed output
-  // columns that are never stored
-  const int lane_off = FMT == FMT_FP16 ? 8 * kq : (REC_K / 4) * kq;
-  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
-  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
-
-  f4 acc[MT];
-#pragma unroll
-  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
-
-  const int XP = a.x_phase;  // a multiple of LR
-  const bool vec_x = (a.K & 7) == 0;
-  constexpr int UNITS_PER_PASS = 64 * XUnit<FMT>::XU;
-  const int n_pass = ((a.M << a.x_shift) + UNITS_PER_PASS - 1) / UNITS_PER_PASS;
-
-  // the first activations are requested ahead of the weight stream
-  XRegs<FMT> xr;
-  if (vec_x) x_load<FMT>(xr, a, r_begin * REC_K, min(XP, r_end - r_begin) * REC_K, 0, lane, 64);
-  __builtin_amdgcn_sched_barrier(0);
-
-  LaneRec<FMT> ring[LR];
-#pragma unroll
-  for (int q = 0; q < LR; q++) {
-    load_rec<FMT>(ring[q], a, strip, min(r_begin + q, r_last), lane);
-    __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
-  }
-
-  for (int xp0 = r_begin; xp0 < r_end; xp0 += XP) {
-    const int xp_cnt = min(XP, r_end - xp0);
-    if (vec_x) {
-      x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, 0, lane, 64);
-      for (int pass = 1; pass < n_pass; pass++) {
-        x_load<FMT>(xr, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane, 64);
-        x_store<FMT>(xr, xs, a, xp0 * REC_K, xp_cnt * REC_K, pass, lane, 64);
-      }
-    } else {
-      stage_x_unaligned<FMT>(xs, a, xp0 * REC_K, xp_cnt * REC_K, lane, 64);
-    }
-    __builtin_amdgcn_wave_barrier();
-    int g = 0;
-    for (; g + LR <= xp_cnt; g += LR) {
-#pragma unroll
-      for (int q = 0; q < LR; q++) {
-        mac_rec<FMT, MT>(ring[q], x0 + (g + q) * REC_K, x1 + (g + q) * REC_K, acc);
-        load_rec<FMT>(ring[q], a, strip, min(xp0 + g + q + LR, r_last), lane);
-        // keep the refill right behind its record: the ring then drains one record at a time
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // fewer than LR records left: this is the wave's last phase
-#pragma unroll
-    for (int q = 0; q < LR - 1; q++)
-      if (g + q < xp_cnt) mac_rec<FMT, MT>(ring[q], x0 + (g + q) * REC_K, x1 + (g + q) * REC_K, acc);
-    __builtin_amdgcn_wave_barrier();
-    if (vec_x && xp0 + XP < r_end) x_load<FMT>(xr, a, (xp0 + XP) * REC_K, min(XP, r_end - xp0 - XP) * REC_K, 0, lane, 64);
-  }
-
-  // cross-wave reduction of the 16 x 16 tiles, then scale, convert, store
-  __syncthreads();
-  f4* red = (f4*)smem;
-#pragma unroll
-  for (int i = 0; i < MT; i++) red[(wave * MT + i) * 64 + lane] = acc[i];
-  __syncthreads();
-  if (tid < 64 * MT) {
-    const int mt = tid >> 6;
-    f4 sum = {0, 0, 0, 0};
-    for (int w = 0; w < S; w++) sum += red[(w * MT + mt) * 64 + lane];
-    const int m = m_lo + 16 * mt;
-    if (m < a.M) {
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int n = strip * 16 + 4 * kq + r;  // C[i][j]: lane = j + 16*(i/4), register i%4
-        if (n < a.N) {
-          float v = sum[r];
-          if constexpr (FMT != FMT_FP16) v *= (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
-          a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)v);
-        }
-      }
-    }
-  }
-}
-
-// Scale a finished 16x16 tile (C[i][j]: lane = j + 16*(i/4), register i%4), convert, store.
-template <int FMT, int MT>
-__device__ __forceinline__ void store_tile(const f4 t[MT], const LinearArgs& a, int strip, int lane) {
-  const int m_lo = lane & 15, kq = lane >> 4;
-#pragma unroll
-  for (int mt = 0; mt < MT; mt++) {
-    const int m = m_lo + 16 * mt;
-    if (m < a.M) {
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int n = strip * 16 + 4 * kq + r;
-        if (n < a.N) {
-          float v = t[mt][r];
-          if constexpr (FMT != FMT_FP16) v *= (float)__builtin_bit_cast(_Float16, a.scales[n]) * kTwo14;
-          a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)v);
-        }
-      }
-    }
   }
 }
 
@@ -1067,62 +943,10 @@ __global__ void __launch_bounds__(1024) read_probe_kernel(const u4* __restrict__
 }
 
 // ---- host-side launch logic -------------------------------------------------
-constexpr int kLdsBudget = 60 * 1024;   // phase kernel: bytes of LDS for staged activations per workgroup
 constexpr int kLdsMaxBytes = 160 * 1024;  // LDS of a gfx950 compute unit
-
-struct Plan {
-  int S, lr, x_phase, x_shift, x_stride, x_region;
-  size_t lds;
-};
-
-// Choose the wavefronts per workgroup (S), the ring depth (LR) and the activation
-// phase length.  The grid should be about one resident round of wavefronts (256 CUs x
-// 4 SIMDs x 4 waves at this kernel's register use): each wave then streams a long run of
-// records through its ring instead of many short-lived workgroups starting and
-// draining in lockstep.
-constexpr int kResidentWaves = 4096;
 
 // activations are staged in units of one permutation block
 int x_unit(int fmt) { return fmt == FMT_FP16 ? 8 : ams::kFormats[fmt].perm_block; }
-
-Plan make_plan(int fmt, int M, int64_t n_strips, int n_rec, int rec_k) {
-  Plan p;
-  const int mt = M > 16 ? 2 : 1;
-  const int64_t total_recs = n_strips * n_rec;
-  const int lr_max = 4;
-  const int per_wave_target = (int)std::min<int64_t>(n_rec, std::max<int64_t>(2, (total_recs + kResidentWaves - 1) / kResidentWaves));
-  int S = std::min(16, std::max(1, (n_rec + per_wave_target - 1) / per_wave_target));
-  S = std::min(S, n_rec);
-  for (;;) {
-    const int per_wave = (n_rec + S - 1) / S;
-    int lr = lr_max;
-    while (lr > 2 && lr > per_wave) lr /= 2;
-    // activation rows a wave can hold: as many records as the LDS budget allows
-    int xp = kLdsBudget / (S * M * rec_k * 2);
-    xp = std::min(xp / lr * lr, (per_wave + lr - 1) / lr * lr);
-    if (xp < lr && lr > 2) {  // shrink the ring before shrinking the workgroup
-      lr = 2;
-      xp = kLdsBudget / (S * M * rec_k * 2);
-      xp = std::min(xp / lr * lr, (per_wave + lr - 1) / lr * lr);
-    }
-    if (xp >= lr || S == 1) {
-      p.S = S;
-      p.lr = lr;
-      p.x_phase = std::max(xp, lr);
-      break;
-    }
-    S = S / 2;
-  }
-  {
-    const int units = p.x_phase * rec_k / x_unit(fmt);
-    p.x_shift = 0;
-    while ((1 << p.x_shift) < units) p.x_shift++;
-  }
-  p.x_stride = p.x_phase * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
-  p.x_region = M * p.x_stride;
-  p.lds = std::max((size_t)p.S * p.x_region * 2, (size_t)p.S * mt * 64 * 16);
-  return p;
-}
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -1295,7 +1119,7 @@ int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hip
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
-enum KernelKind { kSweep, kSweepCached, kSweepGrouped, kStream, kPhase };
+enum KernelKind { kSweep, kSweepCached, kSweepGrouped, kStream };
 
 template <int FMT, int MT>
 int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
@@ -1318,11 +1142,6 @@ int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, 
     switch (lr) {
       case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
       case 2: return launch(stream_kernel<FMT, MT, 2>, a, grid, S, lds, st);
-    }
-  } else {
-    switch (lr) {
-      case 4: return launch(phase_kernel<FMT, MT, 4>, a, grid, S, lds, st);
-      case 2: return launch(phase_kernel<FMT, MT, 2>, a, grid, S, lds, st);
     }
   }
   return AMS_ERR_LAUNCH;
@@ -1383,7 +1202,6 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     }
     a.x_stride = wp.x_stride;
     a.x_region = wp.x_region;
-    a.x_phase = 0;
     a.x_shift = wp.x_shift;
     a.spw = wp.spw;
     a.red_slots = 0;
@@ -1399,7 +1217,6 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   if (sp.ok) {
     a.x_stride = sp.x_stride;
     a.x_region = sp.x_region;
-    a.x_phase = 0;
     a.x_shift = sp.x_shift;
     a.spw = sp.spw;
     a.red_slots = sp.red_slots;
@@ -1409,17 +1226,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     return M <= 16 ? launch_by_ring<FMT, 1>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st)
                    : launch_by_ring<FMT, 2>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st);
   }
-  const Plan p = make_plan(FMT, M, n_strips, n_rec, REC_K);
-  a.x_stride = p.x_stride;
-  a.x_region = p.x_region;
-  a.x_phase = p.x_phase;
-  a.x_shift = p.x_shift;
-  a.spw = 1;
-  a.red_slots = 0;
-  a.piece_q = a.piece_r = 0;
-  a.rc = 0;
-  return M <= 16 ? launch_by_ring<FMT, 1>(kPhase, p.lr, a, (unsigned)n_strips, p.S, p.lds, st)
-                 : launch_by_ring<FMT, 2>(kPhase, p.lr, a, (unsigned)n_strips, p.S, p.lds, st);
+  return AMS_ERR_SHAPE;  // not reached: the contiguous-piece plan accepts every shape the checks above let through
 }
 
 }  // namespace

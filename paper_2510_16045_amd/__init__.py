@@ -63,6 +63,7 @@ def load_library():
     lib.ams_linear_workspace_bytes.argtypes = [_int, _int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.ams_linear_ws.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp, ctypes.c_size_t, _vp]
     lib.ams_fp16_linear_ws.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp, ctypes.c_size_t, _vp]
+    lib.ams_linear_plan.argtypes = [_int, _int, _i64, _i64, _int, ctypes.c_char_p, ctypes.c_size_t]
     lib.ams_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
     _lib = lib
     return lib
@@ -304,3 +305,10 @@ def ams_fp16_linear_ws(W, X, workspace, out=None):
     )
     _check(rc, "ams_fp16_linear_ws")
     return out
+
+
+def ams_linear_plan(fmt: int, M: int, N: int, K: int, with_workspace: bool = False) -> str:
+    """Which kernel and launch shape the library would use for this problem (fmt = -1: the fp16 baseline)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(load_library().ams_linear_plan(fmt, M, N, K, int(with_workspace), buf, len(buf)), "ams_linear_plan")
+    return buf.value.decode()

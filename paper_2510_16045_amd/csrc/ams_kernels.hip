@@ -16,6 +16,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <mutex>
 #include <vector>
 
@@ -1313,6 +1314,31 @@ int ams_linear_workspace_bytes(int fmt, int M, int64_t N, int64_t K, size_t* byt
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + rec_k - 1) / rec_k);
   *bytes = split_workspace_bytes(M, n_strips, choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes));
+  return AMS_OK;
+}
+
+int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, char* text, size_t text_len) {
+  if (!text || text_len == 0) return AMS_ERR_NULL;
+  if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
+  int rec_k = 128, rec_bytes = 4096, f = FMT_FP16;
+  if (fmt >= 0) {
+    const ams::FormatInfo* fi = ams::format_info(fmt);
+    if (!fi) return AMS_ERR_FORMAT;
+    rec_k = fi->rec_k, rec_bytes = fi->rec_bytes, f = fmt;
+  }
+  const int64_t n_strips = (N + 15) / 16;
+  const int n_rec = (int)((K + rec_k - 1) / rec_k);
+  const int gk = with_workspace ? choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes) : 1;
+  const SweepPlan wp = make_sweep_plan(f, M, n_strips, n_rec, rec_k, false, gk);
+  if (wp.ok) {
+    const int slice = (n_rec + gk - 1) / gk;
+    snprintf(text, text_len, "sweep grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu", wp.grid, wp.spw,
+             wp.gk, wp.S, wp.wps, (slice + wp.rc - 1) / wp.rc, wp.lds);
+    return AMS_OK;
+  }
+  const StreamPlan sp = make_stream_plan(f, M, n_strips, n_rec, rec_k);
+  snprintf(text, text_len, "stream grid=%d strips_per_wg=%d k_slices=1 waves=%d phases=%d lds=%zu", sp.grid, sp.spw, sp.S,
+           (n_rec + sp.rc - 1) / sp.rc, sp.lds);
   return AMS_OK;
 }
 

@@ -86,6 +86,8 @@ def test_dequant_bit_exact(fmt, ofmt, maker, N, K):
         (48, 14336, (1, 16)),  # long K: many records per wave
         (528, 4096, (1, 4, 32)),  # M=32 needs several activation phases
         (16, 5, (1,)),
+        (70000, 64, (1, 7)),  # many strips, one record each: 18 strips per workgroup
+        (64, 20000, (3, 17)),  # four strips, very long rows: K in many phases at M=17
     ],
 )
 def test_linear_matches_oracle(fmt, ofmt, N, K, Ms):
@@ -201,7 +203,7 @@ def test_linear_full_size_sampled_rows(fmt, ofmt):
 @pytest.mark.parametrize(
     "N,K,Ms",
     [
-        (28672, 4096, (1, 4, 16)),  # Llama-8B gate/up: 7 strips per workgroup; M=16 walks K in phases
+        (28672, 4096, (1, 4, 16, 32)),  # Llama-8B gate/up: 7 strips per workgroup; M=16 walks K in phases, M=32 takes the contiguous-piece kernel
         (4200, 14336, (1, 8)),  # long K, workgroups with 2 strips and with 1; M=8 walks K in phases
         (8200, 1000, (1, 32)),  # ragged everything, 3 strips per workgroup, two MFMA row tiles
     ],

@@ -194,3 +194,25 @@ def test_padding_is_zero_and_layout_is_deterministic():
         # rows 5..15 and k >= 50 are padding: a matrix of zero codes packs to all-zero bytes
         z = ams.ams_pack_codes(fmt, np.zeros((5, 50), dtype=np.uint8))
         assert not z.any()
+
+
+def test_launch_plans_cover_both_kernels_and_the_split():
+    # host logic only: which kernel a shape is sent to (the GPU tests run these very shapes)
+    plan = lambda *a, **k: dict(kv.split("=") for kv in ams.ams_linear_plan(*a, **k).split()[1:])
+    kind = lambda *a, **k: ams.ams_linear_plan(*a, **k).split()[0]
+    assert kind(ams.FP533, 1, 28672, 4096) == "sweep"
+    p = plan(ams.FP533, 1, 28672, 4096)
+    assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves_per_strip"], p["phases"]) == ("256", "7", "1", "16", "1")
+    assert int(plan(ams.FP533, 16, 28672, 4096)["waves_per_strip"]) < 16  # parked tiles would not fit otherwise
+    assert kind(ams.FP533, 32, 28672, 4096) == "stream"
+    assert int(plan(ams.FP425, 8, 4096, 14336)["phases"]) > 1
+    assert plan(ams.FP425, 8, 4096, 14336, with_workspace=True)["k_slices"] == "4"
+    assert plan(ams.FP425, 1, 4096, 14336, with_workspace=True)["k_slices"] == "1"
+    assert kind(-1, 1, 4096, 4096) == "sweep"
+    for fmt, _ in PAIRS:
+        for M in (1, 7, 16, 17, 32):
+            for N, K in [(1, 1), (16, 5), (37, 1000), (100000, 64), (64, 100000), (1 << 20, 96)]:
+                assert int(plan(fmt, M, N, K)["lds"]) <= 160 * 1024
+                assert int(plan(fmt, M, N, K, with_workspace=True)["lds"]) <= 160 * 1024
+    with pytest.raises(ams.AmsError):
+        ams.ams_linear_plan(ams.FP533, 33, 16, 96)

@@ -216,3 +216,13 @@ def test_launch_plans_cover_both_kernels_and_the_split():
                 assert int(plan(fmt, M, N, K, with_workspace=True)["lds"]) <= 160 * 1024
     with pytest.raises(ams.AmsError):
         ams.ams_linear_plan(ams.FP533, 33, 16, 96)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -81,7 +81,14 @@ __device__ __forceinline__ uint32_t pair_bits_e2m2(uint32_t spread, int t) { ret
 __device__ __forceinline__ void restore_e2m3(uint32_t s, uint32_t sh0, uint32_t sh1, uint32_t sh2, uint32_t out[3]) {
   constexpr uint32_t M = 0x8F008F00u;
   out[0] = bfi(M, s, sh0);
-  out[1] = bfi(0x80008000u, s << 1, ((s << 4) & 0x0F000F00u) | sh1);
+  {
+    // member 1: magnitude and sign need different shifts; spelled out as and-or + bit-field
+    // insert (left to itself the compiler makes two ands and a three-way or: one operation more)
+    uint32_t t, r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(t) : "v"(s << 4), "s"(0x0F000F00u), "v"(sh1));
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "s"(0x80008000u), "v"(s << 1), "v"(t));
+    out[1] = r;
+  }
   out[2] = bfi(M, pk_mul_u16(s & 0x200F200Fu, 0x01040104u), sh2);
 }
 // FP5.33: each half-word is a whole group, its shared bit sits at bit 12

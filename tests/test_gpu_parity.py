@@ -234,6 +234,34 @@ def test_fp16_baseline_matches_oracle(N, K, Ms):
         check_linear(y, O.fp16_linear(W, X), f"fp16 N={N} K={K} M={M}")
 
 
+def test_linear_random_shapes_all_entry_points():
+    # seeded random problems: every format, ragged N and K, any batch, the three Linear entry points
+    rng = np.random.default_rng(2510_16045)
+    ws = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    for case in range(40):
+        fmt, ofmt = PAIRS[int(rng.integers(len(PAIRS)))]
+        N = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 3000)) if case % 4 else int(rng.integers(1, 40))
+        M = int(rng.integers(1, 33))
+        W = synth.gaussian_weights(N, K, 1000 + case)
+        X = synth.activations(M, K, 2000 + case)
+        x = dev(X)
+        what = f"case {case}: fmt {ofmt.name} N={N} K={K} M={M}"
+        packed, scales = ams.ams_pack(fmt, W)
+        codes, o_scales, _ = O.ams_quantize(W, ofmt)
+        ref = O.linear(codes, o_scales, X, ofmt)
+        wp, sc = dev(packed), dev(scales)
+        check_linear(host16(ams.ams_linear(wp, sc, x, N, fmt)), ref, what)
+        check_linear(host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws)), ref, what + " (workspace)")
+        sg = REC_K[fmt] * int(rng.choice([1, 2, 8]))
+        gp, gs = ams.ams_pack_grouped(fmt, W, sg)
+        gcodes, g_scales = O.ams_quantize_grouped(W, ofmt, sg)
+        y = host16(ams.ams_linear_grouped(dev(gp), dev(gs), sg, x, N, fmt))
+        check_linear(y, O.linear(gcodes, g_scales, X, ofmt, sg), what + f" (scale runs of {sg})")
+    torch.cuda.synchronize()
+    assert not ws[: 4 * 16384].any()
+
+
 # ---- K split over workgroups through a workspace -------------------------------------------------
 @pytest.mark.parametrize("fmt,ofmt", PAPER_PAIRS + [(ams.FP433, O.FP433)])
 def test_linear_with_workspace_matches_oracle(fmt, ofmt):

@@ -21,7 +21,9 @@ Conventions
 
 Pinned by tests/test_oracle_*.py (Table 1 values, closed forms, exhaustive
 rounding against the definition, brute force over all shared-bit assignments,
-round trips, k=1 reduction to plain RTN, numpy matmul).  Not pinned: the bit
+round trips, k=1 reduction to plain RTN, numpy matmul; the re-rounding search
+against the format with one mantissa bit less and a brute force over all code
+tuples; scales per run of input channels against scalar arithmetic).  Not pinned: the bit
 order inside the paper's packed words (its figures are not available); only
 the word counts the paper states are asserted ("parity unpinned" for bit
 order, which no result depends on).

@@ -197,7 +197,15 @@ def reround_magnitude_codes(a: np.ndarray, fmt: Format, m0: int) -> np.ndarray:
     return 2 * upper + m0
 
 
-def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64, search: str = "set"):
+def tensor_scales(W: np.ndarray, fmt: Format) -> np.ndarray:
+    """Per-tensor granularity (Sec. 5): Eq. 1 with the maximum taken over the whole
+    matrix; returned once per row so that it can stand in for row_scales."""
+    W = np.asarray(W)
+    flat = row_scales(W.reshape(1, -1), fmt)
+    return np.repeat(flat, W.shape[0])
+
+
+def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64, search: str = "set", per_tensor: bool = False):
     """Channel-wise RTN, grouping along K, adaptive search of the shared bit.
 
     Follows Sec. 3.1 in order: (1) RTN of every weight to FPx with one scale
@@ -213,6 +221,9 @@ def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64, search: str =
     * when K is not a multiple of the group size the last group is shorter:
       only its real members enter the sum (padding is never an output).
 
+    ``per_tensor=True`` uses one scale for the whole matrix (the coarsest
+    granularity Sec. 5 names) instead of one per output channel.
+
     ``search="reround"`` is a variant that is NOT in the paper: for each value
     of the shared bit every member is re-rounded to the nearest code that ends
     in that bit (instead of keeping the upper bits of its RTN code); the rest
@@ -227,7 +238,7 @@ def ams_quantize(W: np.ndarray, fmt: Format, chunk_rows: int = 64, search: str =
     N, K = W.shape
     g = fmt.group
     n_groups = -(-K // g)
-    s = row_scales(W, fmt)
+    s = tensor_scales(W, fmt) if per_tensor else row_scales(W, fmt)
     codes = np.empty((N, K), dtype=np.int64)
     shared = np.empty((N, n_groups), dtype=np.uint8)
     for r0 in range(0, N, chunk_rows):

@@ -347,6 +347,18 @@ def test_grouped_scales_reduce_to_per_channel_and_help_on_heavy_tails(fmt):
         O.dequant_real(c96, s96, fmt, 128)
 
 
+@pytest.mark.parametrize("fmt", AMS)
+def test_per_tensor_scale_is_per_channel_on_the_flattened_matrix(fmt):
+    # with K a multiple of the group size the groups of the flattened matrix are the same groups
+    N, K = 6, 24 * fmt.group
+    W = synth.heavy_tail_weights(N, K, 94)
+    codes, s, shared = O.ams_quantize(W, fmt, per_tensor=True)
+    c1, s1, _ = O.ams_quantize(W.reshape(1, -1), fmt)
+    assert np.all(s == s1[0]) and s.shape == (N,)
+    assert s1[0] == np.float16(np.max(np.abs(W.astype(np.float64))) / O.format_max(fmt))
+    assert np.array_equal(codes, c1.reshape(N, K))
+
+
 def test_worked_groups_fixture():
     names = {"fp4.25": O.FP425, "fp5.33": O.FP533}
     n = 0

@@ -114,6 +114,14 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W_fp16, int64_t N, int64_t 
                 uint16_t* scales_fp16, uint8_t* codes);
 
 /*
+ * ams_pack_ex with ONE scale for the whole matrix (per-tensor granularity, Sec. 5):
+ * s = fp16(max over all of |W| / Fmax).  `scales_fp16` still receives N values (all the
+ * same), so the result is used with ams_dequant / ams_linear unchanged.
+ */
+int ams_pack_per_tensor(int fmt, int search, const uint16_t* W_fp16, int64_t N, int64_t K, int64_t ldw, void* packed,
+                        uint16_t* scales_fp16, uint8_t* codes);
+
+/*
  * One scale per run of `scale_group` consecutive input channels of a row instead of
  * one per row (Sec. 5: the method "can be applied with any granularity ... per-group";
  * read as Eq. 1, RTN and the search applied to every run by itself).  scale_group must

@@ -55,6 +55,7 @@ def load_library():
     lib.ams_pack_grouped.argtypes = [_int, _int, _i64, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
     lib.ams_dequant_grouped.argtypes = [_int, _vp, _vp, _i64, _vp, _i64, _i64, _int, _vp]
     lib.ams_linear_grouped.argtypes = [_vp, _vp, _i64, _vp, _vp, _int, _i64, _i64, _int, _vp]
+    lib.ams_pack_per_tensor.argtypes = [_int, _int, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
     lib.ams_pack_codes.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_unpack_host.argtypes = [_int, _vp, _i64, _i64, _vp]
     lib.ams_dequant.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _int, _vp]
@@ -312,3 +313,17 @@ def ams_linear_plan(fmt: int, M: int, N: int, K: int, with_workspace: bool = Fal
     buf = ctypes.create_string_buffer(256)
     _check(load_library().ams_linear_plan(fmt, M, N, K, int(with_workspace), buf, len(buf)), "ams_linear_plan")
     return buf.value.decode()
+
+
+def ams_pack_per_tensor(fmt: int, W: np.ndarray, search: int = SEARCH_SET_BIT, return_codes: bool = False):
+    """Quantize + pack with one scale for the whole matrix; returns it once per row, like ams_pack."""
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float16 array")
+    W = np.ascontiguousarray(W)
+    N, K = W.shape
+    packed = np.empty(ams_packed_bytes(fmt, N, K), dtype=np.uint8)
+    scales = np.empty(N, dtype=np.float16)
+    codes = np.empty((N, K), dtype=np.uint8) if return_codes else None
+    rc = load_library().ams_pack_per_tensor(fmt, search, _np_ptr(W), N, K, K, _np_ptr(packed), _np_ptr(scales), _np_ptr(codes) if return_codes else None)
+    _check(rc, "ams_pack_per_tensor")
+    return (packed, scales, codes) if return_codes else (packed, scales)

@@ -94,14 +94,27 @@ struct RowQuant {
 
 // Quantize one row: scale (Eq. 1), RTN, adaptive search of each group's shared bit.
 // Returns false on inf/NaN.
-bool quantize_row(const RowQuant& q, const uint16_t* w, int64_t K, uint8_t* codes, uint16_t* scale_out) {
+// Largest magnitude of a run of weights, or a negative number when one of them is inf or NaN.
+double abs_max(const uint16_t* w, int64_t K) {
   double absmax = 0;
   for (int64_t k = 0; k < K; k++) {
-    if (((w[k] >> 10) & 31) == 31) return false;
+    if (((w[k] >> 10) & 31) == 31) return -1.0;
     absmax = std::max(absmax, std::fabs(half_to_double(w[k])));
   }
-  uint16_t sb = double_to_half_bits(absmax / q.fmax);
-  if (sb == 0) sb = 0x3C00;  // a zero scale would not decode: use 1.0
+  return absmax;
+}
+
+// Eq. 1: the fp16 scale for a given largest magnitude (1.0 where it would be zero)
+uint16_t scale_bits(double absmax, double fmax) {
+  const uint16_t sb = double_to_half_bits(absmax / fmax);
+  return sb == 0 ? (uint16_t)0x3C00 : sb;
+}
+
+// forced_scale: 0 = the row's own scale (Eq. 1 per output channel), else the fp16 bits to use
+bool quantize_row(const RowQuant& q, const uint16_t* w, int64_t K, uint8_t* codes, uint16_t* scale_out, uint16_t forced_scale = 0) {
+  const double absmax = abs_max(w, K);
+  if (absmax < 0) return false;
+  const uint16_t sb = forced_scale ? forced_scale : scale_bits(absmax, q.fmax);
   *scale_out = sb;
   const double s = half_to_double(sb);
   const int sign_shift = 2 + q.mbits;
@@ -288,8 +301,24 @@ int ams_pack(int fmt, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void
   return ams_pack_ex(fmt, AMS_SEARCH_SET_BIT, W, N, K, ldw, packed, scales, codes_out);
 }
 
+namespace {
+int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed,
+              uint16_t* scales, uint8_t* codes_out);
+}
+
 int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed, uint16_t* scales,
                 uint8_t* codes_out) {
+  return pack_rows(fmt, search, false, W, N, K, ldw, packed, scales, codes_out);
+}
+
+int ams_pack_per_tensor(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed,
+                        uint16_t* scales, uint8_t* codes_out) {
+  return pack_rows(fmt, search, true, W, N, K, ldw, packed, scales, codes_out);
+}
+
+namespace {
+int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N, int64_t K, int64_t ldw, void* packed,
+              uint16_t* scales, uint8_t* codes_out) {
   if (int rc = check_shape(fmt, N, K)) return rc;
   if (search != AMS_SEARCH_SET_BIT && search != AMS_SEARCH_REROUND) return AMS_ERR_SHAPE;
   if (!W || !packed || !scales) return AMS_ERR_NULL;
@@ -298,6 +327,16 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, in
   const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax, search};
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
   const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
+  uint16_t tensor_scale = 0;
+  if (per_tensor) {  // Eq. 1 with the maximum over the whole matrix
+    double absmax = 0;
+    for (int64_t n = 0; n < N; n++) {
+      const double m = abs_max(W + n * ldw, K);
+      if (m < 0) return AMS_ERR_NONFINITE;
+      absmax = std::max(absmax, m);
+    }
+    tensor_scale = scale_bits(absmax, fi.fmax);
+  }
   std::atomic<int> bad{0};
   parallel_for(n_strips, [&](int64_t t) {
     std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
@@ -309,7 +348,7 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, in
         continue;
       }
       uint8_t* c = buf.data() + (size_t)r * K;
-      if (!quantize_row(rq, W + n * ldw, K, c, scales + n)) bad.store(1);
+      if (!quantize_row(rq, W + n * ldw, K, c, scales + n, tensor_scale)) bad.store(1);
       rows[r] = c;
       if (codes_out) std::memcpy(codes_out + n * K, c, (size_t)K);
     }
@@ -317,6 +356,7 @@ int ams_pack_ex(int fmt, int search, const uint16_t* W, int64_t N, int64_t K, in
   });
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
 }
+}  // namespace
 
 // log2(scale_group / rec_k), or -1 when scale_group is not rec_k * 2^j
 int scale_group_shift(const FormatInfo& fi, int64_t scale_group) {

@@ -139,6 +139,21 @@ def test_grouped_scales_match_oracle_bit_for_bit(fmt, ofmt, N, K, mult, search):
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_per_tensor_scale_matches_oracle_bit_for_bit(fmt, ofmt):
+    W = synth.heavy_tail_weights(37, 500, 29)
+    packed, scales, codes = ams.ams_pack_per_tensor(fmt, W, return_codes=True)
+    o_codes, o_scales, _ = O.ams_quantize(W, ofmt, per_tensor=True)
+    assert np.array_equal(scales.view(np.uint16), o_scales.view(np.uint16)) and len(set(scales.tolist())) == 1
+    assert np.array_equal(codes, o_codes.astype(np.uint8))
+    assert np.array_equal(ams.ams_unpack_host(fmt, packed, 37, 500), codes)
+    Z = np.zeros((3, 8), dtype=np.float16)
+    assert np.all(ams.ams_pack_per_tensor(fmt, Z)[1] == np.float16(1.0))
+    Z[1, 2] = np.float16(np.nan)
+    with pytest.raises(ams.AmsError, match="inf or NaN"):
+        ams.ams_pack_per_tensor(fmt, Z)
+
+
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_degenerate_rows_and_errors(fmt, ofmt):
     W = np.zeros((3, 24), dtype=np.float16)
     W[1, 5] = np.float16(6e-8)

@@ -343,6 +343,9 @@ def main():
             "launch_floor_us": round(launch_floor, 3), "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
         },
         "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
+        # the single-Linear configuration of the baseline list (4096x4096, FP5.33-e2m3, M=1) is the `o` layer of this set
+        "single_linear_4096x4096_fp533_m1": next(({"us": r["us"], "GBps": r["GBps"], "hbm_frac": r["hbm_frac"], "speedup_vs_fp16": r["speedup_vs_fp16"]}
+                                                  for r in per_layer if (r["N"], r["K"], r["fmt"]) == (4096, 4096, FMT_NAMES[0])), None),
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",
     }
     print(json.dumps(line))

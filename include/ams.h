@@ -59,7 +59,7 @@ enum {
 int ams_version(void);
 const char* ams_strerror(int code);
 
-/* Group size k of the format (3 or 4) and bits of one code (6 or 5); 0 for an unknown fmt. */
+/* Group size k of the format (1 to 4) and bits of one code (4 to 6); 0 for an unknown fmt. */
 int ams_group_size(int fmt);
 int ams_code_bits(int fmt);
 
@@ -169,6 +169,7 @@ int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t*
  *   W_packed device (ams_pack layout), scales device [N] fp16,
  *   X device [M, K] fp16 row-major, Y device [M, N] fp16 row-major, 1 <= M <= AMS_MAX_M.
  * All four pointers must be 16-byte aligned.  X and Y must not alias.
+ * Errors: FORMAT, NULL, SHAPE (M, N or K out of range), ALIGN, LAUNCH.
  */
 int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
                int64_t K, int fmt, void* stream);

@@ -224,6 +224,22 @@ def test_linear_large_shapes_sampled_rows(fmt, ofmt, N, K, Ms):
         check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M} sample")
 
 
+def test_linear_70b_gate_up_sampled_rows():
+    # the largest benchmark shape (57344 x 8192, 14 strips per workgroup, 313 MB packed), FP5.33
+    N, K = synth.LLAMA70B_LAYERS["gate_up"]
+    W = synth.gaussian_weights(N, K, 85)
+    packed, scales = ams.ams_pack(ams.FP533, W)
+    wp, sc = dev(packed), dev(scales)
+    rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(11, N, 409)])
+    codes, o_scales, _ = O.ams_quantize(W[rows], O.FP533)
+    del W
+    for M in (1, 8):
+        X = synth.activations(M, K, 86 + M)
+        y = host16(ams.ams_linear(wp, sc, dev(X), N, ams.FP533)).astype(np.float64)
+        assert np.all(np.isfinite(y))
+        check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, O.FP533), f"70B gate/up M={M}")
+
+
 @pytest.mark.parametrize("N,K,Ms", [(256, 768, (1, 2, 4, 8, 16, 32)), (37, 1000, (1, 7, 20)), (40, 14336, (1, 16))])
 def test_fp16_baseline_matches_oracle(N, K, Ms):
     W = synth.gaussian_weights(N, K, 71)

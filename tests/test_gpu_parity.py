@@ -224,6 +224,31 @@ def test_linear_large_shapes_sampled_rows(fmt, ofmt, N, K, Ms):
         check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M} sample")
 
 
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+@pytest.mark.parametrize(
+    "N,K,Ms",
+    [
+        (200, 6000, (16, 17, 32)),  # one strip per workgroup, many phases
+        (90, 6004, (32,)),  # activation rows not 16-byte aligned
+        (4400, 3000, (24, 32)),  # two strips per workgroup, the last workgroup has one
+    ],
+)
+def test_linear_activations_in_several_phases(fmt, ofmt, N, K, Ms):
+    # batches whose activations do not fit in LDS: wavefronts that own a strip, others that stage
+    # the next phase's activations beside them
+    W = synth.gaussian_weights(N, K, 91)
+    packed, scales = ams.ams_pack(fmt, W)
+    wp, sc = dev(packed), dev(scales)
+    rows = np.unique(np.r_[0:32, N - 32 : N, np.arange(5, N, 37)])
+    codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+    for M in Ms:
+        assert "phases=1 " not in ams.ams_linear_plan(fmt, M, N, K)
+        X = synth.activations(M, K, 92 + M)
+        y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt)).astype(np.float64)
+        assert np.all(np.isfinite(y))
+        check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M}")
+
+
 def test_linear_70b_gate_up_sampled_rows():
     # the largest benchmark shape (57344 x 8192, 14 strips per workgroup, 313 MB packed), FP5.33
     N, K = synth.LLAMA70B_LAYERS["gate_up"]

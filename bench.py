@@ -175,7 +175,11 @@ def profile_kernel(args, shapes, torch, ams, synth):
         p, s = ams.ams_pack(fmt, W)
         ps = [to_dev(p, torch) for _ in range(n_copies)]
         sc = to_dev(s, torch)
-        run = lambda i: ams.ams_linear(ps[i % n_copies], sc, x, N, fmt, out=y)
+        if args.workspace:  # the entry point that may split K over workgroups
+            wsp = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+            run = lambda i: ams.ams_linear_ws(ps[i % n_copies], sc, x, N, fmt, wsp, out=y)
+        else:
+            run = lambda i: ams.ams_linear(ps[i % n_copies], sc, x, N, fmt, out=y)
     for i in range(args.steps):
         run(i)
     torch.cuda.synchronize()

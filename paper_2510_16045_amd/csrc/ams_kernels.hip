@@ -959,7 +959,7 @@ int x_unit(int fmt) { return fmt == FMT_FP16 ? 8 : ams::kFormats[fmt].perm_block
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 constexpr int kNumCU = 256;             // MI355X compute units
-constexpr int kStreamLdsMax = 150 * 1024;  // of the 160 KiB a workgroup may use
+constexpr int kStreamLdsMax = kLdsMaxBytes;  // one workgroup per compute unit: all of it (measured: the phases of K this saves pay)
 
 struct StreamPlan {
   bool ok;

@@ -31,6 +31,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+CLOCK_RAMP_S = 0.5  # untimed load before the warm-up steps, so that an idle GPU's clocks are up
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
 # by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77697 + 56) * 1024}
@@ -249,6 +250,13 @@ def main():
         with torch.cuda.graph(g):
             step(c)
         graphs.append(g)
+    # a box that has been idle needs a moment of load before its clocks are up (untimed, before the
+    # W warm-up steps: without it the first figures of a fresh process come out up to 15 % low)
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < CLOCK_RAMP_S:
+        for c in range(n_copies):
+            graphs[c].replay()
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         graphs[i % n_copies].replay()
     torch.cuda.synchronize()
@@ -344,7 +352,7 @@ def main():
             if args.layers == "8b" else f"{args.layers} layer set, M=1, both formats",
             "linears_per_step": len(layers) * len(fmts), "packed_bytes_per_step": step_bytes,
             "hbm_peak_GBps": HBM_PEAK_GBPS, "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
-            "launch_floor_us": round(launch_floor, 3), "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
+            "launch_floor_us": round(launch_floor, 3), "clock_ramp_s": CLOCK_RAMP_S, "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
         },
         "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
         # the single-Linear configuration of the baseline list (4096x4096, FP5.33-e2m3, M=1) is the `o` layer of this set

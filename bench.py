@@ -31,6 +31,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+ROTATE_BYTES = 512 << 20  # a Linear timed alone rotates over copies of its weights worth at least this (2 x the 256 MB last-level cache)
 CLOCK_RAMP_S = 0.5  # untimed load before the warm-up steps, so that an idle GPU's clocks are up
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
 # by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
@@ -72,11 +73,14 @@ class Layer:
         for fmt in fmts:
             p, s = ams.ams_pack(fmt, W)
             base = to_dev(p, torch)
-            self.packed[fmt] = [base] + [base.clone() for _ in range(n_copies - 1)]
+            # timed alone, a layer rotates over its own copies: at least twice the last-level cache
+            n = max(n_copies, -(-ROTATE_BYTES // base.numel()))
+            self.packed[fmt] = [base] + [base.clone() for _ in range(n - 1)]
             self.scales[fmt] = to_dev(s, torch)
             self.canon[fmt] = ams.ams_canonical_bytes(fmt, N, K)
         w = to_dev(W, torch)
-        self.w16 = [w] + [w.clone() for _ in range(fp16_copies - 1)]
+        n16 = max(fp16_copies, -(-ROTATE_BYTES // (2 * w.numel())))
+        self.w16 = [w] + [w.clone() for _ in range(n16 - 1)]
         self.W = W  # host copy, for the variants packed on demand
 
 
@@ -273,13 +277,13 @@ def main():
     per_layer = []
     n_launch = 8 * n_copies
     for l in layers:
-        t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % fp16_copies], xs[l.name], ys[l.name]), n_launch)
-        tlib = time_launches(torch, lambda i: torch.matmul(xs[l.name], l.w16[i % fp16_copies].t(), out=ys[l.name]), n_launch)
+        t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % len(l.w16)], xs[l.name], ys[l.name]), n_launch)
+        tlib = time_launches(torch, lambda i: torch.matmul(xs[l.name], l.w16[i % len(l.w16)].t(), out=ys[l.name]), n_launch)
         for fmt in all_fmts:
-            t, pct = time_launches(torch, lambda i: linear(l.packed[fmt][i % n_copies], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name]), n_launch, replays=10, spread=True)
+            t, pct = time_launches(torch, lambda i: linear(l.packed[fmt][i % len(l.packed[fmt])], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name]), n_launch, replays=10, spread=True)
             warm = time_launches(torch, lambda i: linear(l.packed[fmt][0], l.scales[fmt], xs[l.name], l.N, fmt, ys[l.name]), n_launch)
             # second denominator: a bare read of the same packed bytes (same rotation), nothing computed
-            t_read = time_launches(torch, lambda i: ams.ams_read_probe(l.packed[fmt][i % n_copies]), n_launch)
+            t_read = time_launches(torch, lambda i: ams.ams_read_probe(l.packed[fmt][i % len(l.packed[fmt])]), n_launch)
             t_grouped = None
             if args.group_scales:
                 sg = 96 if fmt in (ams.FP533, ams.FP433, ams.FP6) else 128
@@ -310,7 +314,7 @@ def main():
     dl = next(l for l in layers if l.name == dom["layer"])
     dfmt = next(f for f, n in FMT_NAMES.items() if n == dom["fmt"])
     alg_bytes = dl.canon[dfmt] + 2 * dl.N + 2 * M * dl.K + 2 * M * dl.N
-    t_dom = time_launches(torch, lambda i: linear(dl.packed[dfmt][i % n_copies], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, ys[dl.name]), n_launch, replays=20)
+    t_dom = time_launches(torch, lambda i: linear(dl.packed[dfmt][i % len(dl.packed[dfmt])], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
     roofline = {
         "bound": "hbm", "kernel": f"sweep_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
@@ -329,10 +333,10 @@ def main():
             for Mb in (1, 2, 4, 8, 16, 32):
                 x = to_dev(synth.activations(Mb, l.K, 9), torch)
                 y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
-                t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % fp16_copies], x, y), n_launch)
-                tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % fp16_copies].t(), out=y), n_launch)
+                t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % len(l.w16)], x, y), n_launch)
+                tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % len(l.w16)].t(), out=y), n_launch)
                 for fmt in all_fmts:
-                    t = time_launches(torch, lambda i: linear(l.packed[fmt][i % n_copies], l.scales[fmt], x, l.N, fmt, y), n_launch)
+                    t = time_launches(torch, lambda i: linear(l.packed[fmt][i % len(l.packed[fmt])], l.scales[fmt], x, l.N, fmt, y), n_launch)
                     sweep.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
                                   "GBps": round(l.canon[fmt] / t / 1e3, 1), "fp16_us": round(t16, 3),
                                   "library_gemm_fp16_us": round(tlib, 3), "speedup_vs_fp16": round(t16 / t, 3),

@@ -61,3 +61,4 @@ def test_decoder_layer_linears_replay_like_eager(M, use_ws):
             assert torch.equal(y.view(torch.int16), w.view(torch.int16)), f"eager after replay {r}"
     if ws is not None:
         assert not ws[: 4 * 16384].any()
+

@@ -233,6 +233,34 @@ def test_launch_plans_cover_both_kernels_and_the_split():
         ams.ams_linear_plan(ams.FP533, 33, 16, 96)
 
 
+def test_launch_plans_random_shapes_stay_inside_the_machine():
+    # seeded random shapes, every format and the baseline, with and without a workspace: the plan
+    # must exist, fit the 160 KiB of LDS, use at most 16 wavefronts and a grid the kernel can index
+    rng = np.random.default_rng(7)
+    fmts = [f for f, _ in PAIRS] + [-1]
+    for _ in range(1500):
+        fmt = fmts[int(rng.integers(len(fmts)))]
+        M = int(rng.integers(1, 33))
+        N = int(2 ** rng.uniform(0, 20))
+        K = int(2 ** rng.uniform(0, 17))
+        if fmt == -1:
+            K = max(8, K // 8 * 8)
+        for ws in (False, True):
+            text = ams.ams_linear_plan(fmt, M, N, K, with_workspace=ws)
+            kind, kv = text.split()[0], dict(x.split("=") for x in text.split()[1:])
+            assert kind in ("sweep", "stream"), text
+            assert 0 < int(kv["lds"]) <= 160 * 1024, text
+            assert 1 <= int(kv["waves"]) <= 16 and int(kv["phases"]) >= 1 and int(kv["grid"]) >= 1, text
+            n_strips = -(-N // 16)
+            assert int(kv["strips_per_wg"]) * int(kv["grid"]) >= n_strips * int(kv["k_slices"]) or kind == "stream", text
+            if kind == "sweep":
+                assert 16 % int(kv["waves_per_strip"]) == 0 or int(kv["waves_per_strip"]) == int(kv["waves"]), text
+            if not ws:
+                assert kv["k_slices"] == "1", text
+            need = ams.ams_linear_workspace_bytes(fmt, M, N, K)
+            assert (need > 0) == (ws and int(kv["k_slices"]) > 1) or not ws, text
+
+
 def test_bench_refuses_more_than_one_gpu():
     import os
     import subprocess

@@ -233,6 +233,56 @@ def test_launch_plans_cover_both_kernels_and_the_split():
         ams.ams_linear_plan(ams.FP533, 33, 16, 96)
 
 
+def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 and the host entry points must be
+    # callable from a program that has never heard of Python (no device call here)
+    import os
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2510_16045_amd")
+    src = tmp_path / "abi.c"
+    src.write_text(
+        """
+#include "ams.h"
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+int main(void) {
+  size_t bytes = 0, canon = 0;
+  const int64_t N = 20, K = 100;
+  uint16_t W[20 * 100];
+  uint16_t scales[20];
+  uint8_t codes[20 * 100], back[20 * 100];
+  void* packed;
+  int i;
+  for (i = 0; i < 20 * 100; i++) W[i] = (uint16_t)(0x2000 + 37 * i % 0x1400 + ((i & 1) << 15)); /* small fp16 values of both signs */
+  if (ams_packed_bytes(AMS_FMT_FP425_E2M2, N, K, &bytes) != AMS_OK || ams_canonical_bytes(AMS_FMT_FP425_E2M2, N, K, &canon) != AMS_OK) return 1;
+  packed = malloc(bytes);
+  if (ams_pack(AMS_FMT_FP425_E2M2, W, N, K, K, packed, scales, codes) != AMS_OK) return 2;
+  if (ams_unpack_host(AMS_FMT_FP425_E2M2, packed, N, K, back) != AMS_OK) return 3;
+  if (memcmp(codes, back, sizeof codes) != 0) return 4;
+  if (ams_pack(99, W, N, K, K, packed, scales, codes) == AMS_OK) return 5;
+  printf("%d %lu %lu %s\\n", ams_version(), (unsigned long)bytes, (unsigned long)canon, ams_strerror(AMS_OK));
+  free(packed);
+  return 0;
+}
+"""
+    )
+    exe = tmp_path / "abi"
+    cc = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                         "-L", libdir, "-lams", f"-Wl,-rpath,{libdir}"], capture_output=True, text=True)
+    assert cc.returncode == 0, cc.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    version, bytes_, canon, _ = r.stdout.split(None, 3)
+    assert int(bytes_) == ams.ams_packed_bytes(ams.FP425, 20, 100) and int(canon) == 34 * 2 * 20
+
+
 def test_launch_plans_random_shapes_stay_inside_the_machine():
     # seeded random shapes, every format and the baseline, with and without a workspace: the plan
     # must exist, fit the 160 KiB of LDS, use at most 16 wavefronts and a grid the kernel can index

@@ -1031,9 +1031,13 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
   if (any_shape) p.spw = (int)std::max<int64_t>(1, std::min<int64_t>(p.spw, (48 * 1024) / tile_bytes));
   p.gn = (int)((n_strips + p.spw - 1) / p.spw);
   p.grid = p.gn * gk;
-  p.S = (int)std::min<int64_t>(16, (int64_t)p.spw * (n_rec_all / gk));  // n_rec_all / gk: the shortest slice
+  // The baseline's records are four times larger (one in flight per wave).  Measured: at M <= 4 with every
+  // compute unit busy it reads 8-14 % faster from 8 wavefronts with two records in flight each (the packed
+  // formats do not: equal at M = 1, slower from M = 8).
+  const bool few_waves = fmt == FMT_FP16 && M <= 4 && gk == 1 && !any_shape && n_strips >= kNumCU;
+  p.S = (int)std::min<int64_t>(few_waves ? 8 : 16, (int64_t)p.spw * (n_rec_all / gk));  // n_rec_all / gk: the shortest slice
   if (p.S < 1) return p;
-  p.lr = fmt == FMT_FP16 ? 1 : 2;  // the baseline's records are four times larger
+  p.lr = fmt == FMT_FP16 ? (few_waves ? 2 : 1) : 2;
   // waves per strip: all of them unless the parked tiles (one per strip and wave of its group)
   // would take more than 48 KB; never fewer than leaves every group of waves a strip
   p.wps = p.S;
@@ -1141,6 +1145,7 @@ int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, 
       if (lr == 1)
         return groups ? launch(sweep_kernel<FMT, MT, 1, false, false, true>, a, grid, S, lds, st)
                       : launch(sweep_kernel<FMT, MT, 1, false, false, false>, a, grid, S, lds, st);
+      if (lr == 2 && !groups) return launch(sweep_kernel<FMT, MT, 2, false, false, false>, a, grid, S, lds, st);
     } else if (lr == 2) {
       if (groups) return launch(sweep_kernel<FMT, MT, 2, true, false, true>, a, grid, S, lds, st);
       return kind == kSweep ? launch(sweep_kernel<FMT, MT, 2, true>, a, grid, S, lds, st)

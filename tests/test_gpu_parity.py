@@ -265,7 +265,10 @@ def test_linear_70b_gate_up_sampled_rows():
         check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, O.FP533), f"70B gate/up M={M}")
 
 
-@pytest.mark.parametrize("N,K,Ms", [(256, 768, (1, 2, 4, 8, 16, 32)), (37, 1000, (1, 7, 20)), (40, 14336, (1, 16))])
+@pytest.mark.parametrize(
+    "N,K,Ms",
+    [(256, 768, (1, 2, 4, 8, 16, 32)), (37, 1000, (1, 7, 20)), (40, 14336, (1, 16)), (4200, 1000, (1, 4, 5))],  # the last: every CU busy
+)
 def test_fp16_baseline_matches_oracle(N, K, Ms):
     W = synth.gaussian_weights(N, K, 71)
     w = dev(W)

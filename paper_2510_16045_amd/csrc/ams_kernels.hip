@@ -1034,7 +1034,7 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
   // The baseline's records are four times larger (one in flight per wave).  Measured: at M <= 4 with every
   // compute unit busy it reads 8-14 % faster from 8 wavefronts with two records in flight each (the packed
   // formats do not: equal at M = 1, slower from M = 8).
-  const bool few_waves = fmt == FMT_FP16 && M <= 4 && gk == 1 && !any_shape && n_strips >= kNumCU;
+  const bool few_waves = fmt == FMT_FP16 && M <= 4 && gk == 1 && !any_shape && n_strips >= kNumCU && p.spw <= 16;
   p.S = (int)std::min<int64_t>(few_waves ? 8 : 16, (int64_t)p.spw * (n_rec_all / gk));  // n_rec_all / gk: the shortest slice
   if (p.S < 1) return p;
   p.lr = fmt == FMT_FP16 ? (few_waves ? 2 : 1) : 2;

@@ -1049,8 +1049,9 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
     const size_t lds = (size_t)M * x_stride * 2 + parts;
     if (lds > (size_t)kStreamLdsMax) continue;
-    // measured: with many parked tiles and more than two phases the contiguous-piece kernel is faster
-    if (!any_shape && n_phase > 2 && parts > 32 * 1024) break;
+    // measured: with many parked tiles and more than four phases (two for the baseline's larger records) the
+    // contiguous-piece kernel is faster
+    if (!any_shape && n_phase > (fmt == FMT_FP16 ? 2 : 4) && parts > 32 * 1024) break;
     p.ok = true;
     p.rc = rc;
     p.x_stride = x_stride;

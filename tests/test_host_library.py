@@ -219,7 +219,8 @@ def test_launch_plans_cover_both_kernels_and_the_split():
     p = plan(ams.FP533, 1, 28672, 4096)
     assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves_per_strip"], p["phases"]) == ("256", "7", "1", "16", "1")
     assert int(plan(ams.FP533, 16, 28672, 4096)["waves_per_strip"]) < 16  # parked tiles would not fit otherwise
-    assert kind(ams.FP533, 32, 28672, 4096) == "stream"
+    assert kind(ams.FP533, 32, 28672, 4096) == "sweep" and int(plan(ams.FP533, 32, 28672, 4096)["phases"]) <= 4
+    assert kind(ams.FP533, 32, 57344, 8192) == "stream"  # many parked tiles and more than four phases
     assert int(plan(ams.FP425, 8, 4096, 14336)["phases"]) > 1
     assert plan(ams.FP425, 8, 4096, 14336, with_workspace=True)["k_slices"] == "4"
     assert plan(ams.FP425, 1, 4096, 14336, with_workspace=True)["k_slices"] == "1"

@@ -278,6 +278,36 @@ def test_fp16_baseline_matches_oracle(N, K, Ms):
         check_linear(y, O.fp16_linear(W, X), f"fp16 N={N} K={K} M={M}")
 
 
+def test_linear_random_large_shapes_sampled_rows():
+    # seeded random problems large enough to reach every launch plan (wave groups, several phases of K,
+    # the contiguous-piece kernel, the split of K): sampled rows against the oracle, with and without a workspace
+    rng = np.random.default_rng(16045)
+    ws = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    kinds = set()
+    for case in range(15):
+        fmt, ofmt = PAIRS[int(rng.integers(len(PAIRS)))]
+        N = int(2 ** rng.uniform(9, 13.2))
+        K = min(int(2 ** rng.uniform(9, 15)), (40 << 20) // N)
+        M = int(rng.choice([1, 3, 8, 13, 16, 17, 24, 32]))
+        if case == 14:  # three strips per workgroup, large tiles, five phases: the contiguous-piece kernel
+            N, K, M = 8200, 8000, 32
+        print(f"case {case}: fmt {ofmt.name} N={N} K={K} M={M}", flush=True)
+        W = synth.gaussian_weights(N, K, 3000 + case)
+        X = synth.activations(M, K, 4000 + case)
+        packed, scales = ams.ams_pack(fmt, W)
+        rows = np.unique(np.r_[0:16, N - 16 : N, rng.integers(0, N, 24)])
+        codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+        ref = O.linear(codes, o_scales, X, ofmt)
+        wp, sc, x = dev(packed), dev(scales), dev(X)
+        what = f"case {case}: fmt {ofmt.name} N={N} K={K} M={M}"
+        for use_ws in (False, True):
+            kinds.add(ams.ams_linear_plan(fmt, M, N, K, with_workspace=use_ws).split()[0])
+            y = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws) if use_ws else ams.ams_linear(wp, sc, x, N, fmt)).astype(np.float64)
+            assert np.all(np.isfinite(y)), what
+            check_linear(y[:, rows].astype(np.float16), ref, what + (" (workspace)" if use_ws else ""))
+    assert kinds == {"sweep", "stream"}  # the draw reaches both kernels
+
+
 def test_linear_random_shapes_all_entry_points():
     # seeded random problems: every format, ragged N and K, any batch, the three Linear entry points
     rng = np.random.default_rng(2510_16045)

@@ -8,7 +8,8 @@
  * multiplied by a skinny fp16 activation matrix (Sec. 3.3, Sec. 4.2).
  *
  * Conventions for every entry point
- *   - Return value: 0 (AMS_OK) or a negative AMS_ERR_* code; nothing throws or aborts.
+ *   - Return value: 0 (AMS_OK) or a negative AMS_ERR_* code; nothing throws or aborts
+ *     (the host quantizer reports AMS_ERR_NOMEM when it cannot get its row buffers).
  *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
  *     memory of the current device.  The caller owns every buffer.
  *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as
@@ -51,21 +52,36 @@ enum {
   AMS_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned */
   AMS_ERR_NONFINITE = -5, /* a weight is inf or NaN */
   AMS_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch (see hipGetLastError) */
-  AMS_ERR_DEVICE = -7     /* the current device is not a gfx950 GPU */
+  AMS_ERR_DEVICE = -7,    /* the current device is not a gfx950 GPU (returned by every device entry point) */
+  AMS_ERR_NOMEM = -9      /* a host entry point could not get the memory for its row buffers */
 };
 
 #define AMS_MAX_M 32 /* largest activation batch of ams_linear / ams_fp16_linear (Table 3: batch 1..32) */
 
+/* Version of the library and of its packed layout: 100 * major + minor.  A packed buffer is only valid
+ * for the major version that wrote it (200: FP4.25 records carry their shared bits inside the lane chunks). */
 int ams_version(void);
 const char* ams_strerror(int code);
 
-/* Group size k of the format (1 to 4) and bits of one code (4 to 6); 0 for an unknown fmt. */
+/*
+ * Optional one-time set-up for the current device: checks that it is a gfx950 (else
+ * AMS_ERR_DEVICE) and raises the dynamic-LDS limit of every Linear kernel (they use up to
+ * 160 KiB).  Every device entry point does the same for itself on its first call, so this
+ * is only REQUIRED before the first call of an entry point happens inside a HIP stream
+ * capture (function attributes should not be changed while capturing).  Allocates nothing,
+ * enqueues nothing; may be called any number of times, once per device that is used.
+ */
+int ams_init(void);
+
+/* Group size k of the format (Sec. 3.1: the k weights that share their last mantissa bit; 1 to 4, 1 = plain
+ * mini-float) and bits of one code (Sec. 2.2: sign + 2 exponent bits + mantissa; 4 to 6); 0 for an unknown fmt. */
 int ams_group_size(int fmt);
 int ams_code_bits(int fmt);
 
 /*
  * Size in bytes of the packed weight buffer in this library's gfx950 layout
- * (what ams_pack writes and ams_dequant / ams_linear read).  The layout is opaque:
+ * (what ams_pack writes and ams_dequant / ams_linear read): the result of the
+ * "ahead-of-time weight packing" of Sec. 3.3 stage 1, arranged for 64-wide wavefronts.  The layout is opaque:
  * records of 16 rows x 96 weights (FP5.33, FP4.33, FP6) or 16 rows x 128 weights
  * (FP4.25, FP4.5, FP5, FP4), so N is padded to a multiple of 16 and K to a multiple of
  * 96 / 128; padding holds zero codes.  Without padding the size is exactly
@@ -145,13 +161,15 @@ int ams_linear_grouped(const void* W_packed, const uint16_t* scales, int64_t sca
                        int M, int64_t N, int64_t K, int fmt, void* stream);
 
 /*
- * Pack codes that were produced elsewhere (e.g. read from the paper's layout) into
+ * The packing step alone (Sec. 3.3 stage 1; Sec. 3.2: remainders and shared bits stored in
+ * standard words): pack codes that were produced elsewhere (e.g. read from the paper's layout) into
  * the gfx950 layout.  codes [N, K] as written by ams_pack; within a group all last
  * bits must agree (else AMS_ERR_SHAPE).  Host pointers.
  */
 int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* packed);
 
-/* Inverse of the layout step: packed (host) -> codes [N, K] (host).  Debug / tests. */
+/* Inverse of the layout step (the stitching of remainder and shared bit of Sec. 3.2 / Sec. 3.3 stage 2, done on
+ * the host): packed (host) -> codes [N, K] (host).  Debug / tests. */
 int ams_unpack_host(int fmt, const void* packed, int64_t N, int64_t K, uint8_t* codes);
 
 /*
@@ -169,7 +187,9 @@ int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t*
  *   W_packed device (ams_pack layout), scales device [N] fp16,
  *   X device [M, K] fp16 row-major, Y device [M, N] fp16 row-major, 1 <= M <= AMS_MAX_M.
  * All four pointers must be 16-byte aligned.  X and Y must not alias.
- * Errors: FORMAT, NULL, SHAPE (M, N or K out of range), ALIGN, LAUNCH.
+ * Errors: FORMAT, NULL, SHAPE (M, N or K out of range), ALIGN, DEVICE, LAUNCH.
+ * The first call of a kernel on a device raises that kernel's LDS limit: if it can happen inside a
+ * stream capture, call ams_init() before.
  */
 int ams_linear(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
                int64_t K, int fmt, void* stream);

@@ -43,6 +43,7 @@ def load_library():
         raise AmsError(f"{_LIB_PATH} is missing: build it with `python __graft_entry__.py`")
     lib = ctypes.CDLL(_LIB_PATH)
     lib.ams_version.restype = _int
+    lib.ams_init.restype = _int
     lib.ams_strerror.restype = ctypes.c_char_p
     lib.ams_strerror.argtypes = [_int]
     lib.ams_group_size.argtypes = [_int]
@@ -81,6 +82,11 @@ def _np_ptr(a: np.ndarray):
 
 def ams_version() -> int:
     return load_library().ams_version()
+
+
+def ams_init() -> None:
+    """Check the current device and raise the kernels' LDS limits (needed only before a first call under stream capture)."""
+    _check(load_library().ams_init(), "ams_init")
 
 
 def ams_packed_bytes(fmt: int, N: int, K: int) -> int:

@@ -225,28 +225,37 @@ int check_shape(int fmt, int64_t N, int64_t K) {
   return AMS_OK;
 }
 
+// Runs body(0 .. n-1) on up to 16 threads.  False when a body threw (the only thing these bodies can
+// throw is std::bad_alloc from their row buffers); a thread that cannot be started just means fewer workers.
 template <class F>
-void parallel_for(int64_t n, F&& body) {
+bool parallel_for(int64_t n, F&& body) {
   unsigned hw = std::thread::hardware_concurrency();
   int64_t nt = std::max<int64_t>(1, std::min<int64_t>({(int64_t)(hw ? hw : 1), (int64_t)16, n}));
-  if (nt == 1) {
-    for (int64_t i = 0; i < n; i++) body(i);
-    return;
-  }
   std::atomic<int64_t> next{0};
+  std::atomic<int> failed{0};
+  auto work = [&] {
+    try {
+      for (int64_t i; !failed.load() && (i = next.fetch_add(1)) < n;) body(i);
+    } catch (...) {
+      failed.store(1);
+    }
+  };
   std::vector<std::thread> th;
-  for (int64_t t = 0; t < nt; t++)
-    th.emplace_back([&] {
-      for (int64_t i; (i = next.fetch_add(1)) < n;) body(i);
-    });
+  try {
+    th.reserve((size_t)nt);
+    for (int64_t t = 1; t < nt; t++) th.emplace_back(work);
+  } catch (...) {  // no more threads (or no memory for the list): the ones that exist, and this one, do the work
+  }
+  work();
   for (auto& t : th) t.join();
+  return failed.load() == 0;
 }
 
 }  // namespace
 
 extern "C" {
 
-int ams_version(void) { return 100; }
+int ams_version(void) { return 200; }
 
 const char* ams_strerror(int code) {
   switch (code) {
@@ -258,6 +267,7 @@ const char* ams_strerror(int code) {
     case AMS_ERR_NONFINITE: return "weight is inf or NaN";
     case AMS_ERR_LAUNCH: return "kernel launch failed";
     case AMS_ERR_DEVICE: return "current device is not gfx950";
+    case AMS_ERR_NOMEM: return "out of host memory";
     default: return "unknown error";
   }
 }
@@ -338,7 +348,7 @@ int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N
     tensor_scale = scale_bits(absmax, fi.fmax);
   }
   std::atomic<int> bad{0};
-  parallel_for(n_strips, [&](int64_t t) {
+  const bool done = parallel_for(n_strips, [&](int64_t t) {
     std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
     const uint8_t* rows[16];
     for (int r = 0; r < 16; r++) {
@@ -354,6 +364,7 @@ int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N
     }
     pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
   });
+  if (!done) return AMS_ERR_NOMEM;
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
 }
 }  // namespace
@@ -387,7 +398,7 @@ int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W
   const int64_t n_sg = (K + scale_group - 1) / scale_group;
   const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   std::atomic<int> bad{0};
-  parallel_for(n_strips, [&](int64_t t) {
+  const bool done = parallel_for(n_strips, [&](int64_t t) {
     std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
     const uint8_t* rows[16];
     for (int r = 0; r < 16; r++) {
@@ -408,6 +419,7 @@ int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W
     }
     pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
   });
+  if (!done) return AMS_ERR_NOMEM;
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
 }
 

@@ -17,6 +17,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -855,20 +856,24 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
       // result does not depend on who was last), finishes the strip and clears the counter
       // for the next call.  Nobody waits for anybody.
       // The tiles travel as device-scope relaxed atomic stores and loads (they go to the level
-      // of the memory system all compute units share) and the count is taken only after the
-      // stores have been acknowledged; a device-scope fence would instead write back and
-      // invalidate the whole L2, which costs more than the Linear itself.
+      // of the memory system all compute units share).  What orders them: the wave waits until
+      // every one of its tile stores has been acknowledged (s_waitcnt vmcnt(0): on this target
+      // stores count in vmcnt) before it counts itself in, and the last arriver's tile loads are
+      // issued only after its own count has come back (the branch below depends on it).  A
+      // device-scope fence would instead write back and invalidate the whole L2, which costs
+      // more than the Linear itself.
       float* wt = (float*)(a.ws_tiles + ((size_t)gk * a.n_strips + strip) * MT * 64 + lane);
 #pragma unroll
       for (int t = 0; t < MT; t++)
 #pragma unroll
         for (int r = 0; r < 4; r++) __hip_atomic_store(wt + t * 256 + r, sum[t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // waits for the stores above
+      // all tile stores of this wave acknowledged; the compiler moves no memory access across either statement
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       unsigned before = 0;
       if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       before = __builtin_amdgcn_readfirstlane(before);
       if (before != (unsigned)a.gk - 1) continue;
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the loads below stay behind the count
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the count has returned; the tile loads below are issued after it
 #pragma unroll
       for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
       for (int q = 0; q < a.gk; q++) {
@@ -934,7 +939,9 @@ __global__ void __launch_bounds__(1024) read_probe_kernel(const u4* __restrict__
   const int S = blockDim.x >> 6;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t first = (int64_t)blockIdx.x * S + wave, step = (int64_t)gridDim.x * S;
-  const int64_t last = n_rec - 1;
+  // nothing to read (the launch-floor mode) or no record for this wave: no load at all
+  if (first >= n_rec) return;
+  const int64_t last = n_rec - 1;  // >= 0 here; every index below is clamped into [0, last]
   u4 ring[2];
   uint32_t acc = 0;
 #pragma unroll
@@ -1074,6 +1081,8 @@ size_t split_workspace_bytes(int M, int64_t n_strips, int gk) {
   return gk <= 1 ? 0 : kSplitCounterBytes + (size_t)gk * n_strips * (M > 16 ? 2 : 1) * 1024;
 }
 
+constexpr int kMaxSplit = 8;  // most slices of K choose_split ever takes
+
 // How many slices of K to use when a workspace is available.  A split pays when the strips
 // alone do not fill the compute units evenly (e.g. 320 strips: 2 per workgroup on 160 CUs,
 // against 5 strips x a quarter of K on 256) and when the batch is large (every workgroup
@@ -1086,7 +1095,7 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
   if (M < 4) return 1;
   int best = 1;
   double best_cost = 0;
-  for (int gk = 1; gk <= 8; gk *= 2) {
+  for (int gk = 1; gk <= kMaxSplit; gk *= 2) {
     if (gk > 1 && (n_rec / gk < 8 || n_strips > kSplitMaxStrips)) break;
     const SweepPlan p = make_sweep_plan(fmt, M, n_strips, n_rec, rec_k, false, gk);
     int spw = p.spw, rc = p.rc;
@@ -1106,6 +1115,35 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
   return best;
 }
 
+// Per-device state, set up once per device with that device current: whether it is the GPU
+// this library is written for.
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+  int status;     // 0 = not looked at yet, 1 = usable, -1 = not a gfx950 with the expected resources
+};
+std::mutex g_dev_mu;
+DeviceState g_dev[kMaxDevices];
+
+// AMS_OK when the current device is a gfx950 with the compute units and LDS the launch plans
+// assume; looked up once per device (no allocation, no synchronisation).
+int device_state(DeviceState** out = nullptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AMS_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_dev_mu);
+  DeviceState& d = g_dev[dev];
+  if (d.status == 0) {
+    hipDeviceProp_t prop;
+    d.status = -1;
+    if (hipGetDeviceProperties(&prop, dev) == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) == 0 &&
+        prop.multiProcessorCount >= 1 && prop.warpSize == 64) {
+      d.status = 1;
+    }
+    (void)hipGetLastError();  // a failed query must not be reported by the caller's next HIP call
+  }
+  if (out) *out = &d;
+  return d.status == 1 ? AMS_OK : AMS_ERR_DEVICE;
+}
+
 // Kernels that use more than 64 KiB of dynamic LDS must have their limit raised first;
 // that is a per-function, per-device property, remembered here so it is done once.
 bool raise_lds_limit(const void* kern) {
@@ -1121,13 +1159,18 @@ bool raise_lds_limit(const void* kern) {
   for (const Entry& e : done)
     if (e.kern == kern && e.dev == dev) return true;
   if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMaxBytes) != hipSuccess) return false;
-  done.push_back({kern, dev});
+  try {
+    done.push_back({kern, dev});
+  } catch (...) {  // out of host memory: the limit is raised, it is just not remembered
+  }
   return true;
 }
 
+// grid == 0: only prepare the kernel (raise its LDS limit), launch nothing (ams_init)
 template <class Kern>
 int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
-  if (lds > 64 * 1024 && !raise_lds_limit((const void*)kern)) return AMS_ERR_LAUNCH;
+  if ((grid == 0 || lds > 64 * 1024) && !raise_lds_limit((const void*)kern)) return AMS_ERR_LAUNCH;
+  if (grid == 0) return AMS_OK;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * S), lds, st, a);
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
@@ -1168,6 +1211,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (FMT == FMT_FP16 && (K % 8) != 0) return AMS_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(X) || !aligned16(Y) || (scales && !aligned16(scales))) return AMS_ERR_ALIGN;
+  if (const int rc = device_state(); rc != AMS_OK) return rc;
   constexpr int REC_K = Fmt<FMT>::REC_K;
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + REC_K - 1) / REC_K);
@@ -1245,9 +1289,38 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   return AMS_ERR_SHAPE;  // not reached: the contiguous-piece plan accepts every shape the checks above let through
 }
 
+// Raise the LDS limit of every Linear kernel of one weight format on the current device.
+template <int FMT>
+int prepare_format() {
+  LinearArgs a = {};
+  for (int groups = 0; groups < 2; groups++) {
+    a.wps = groups ? 8 : 16;
+    for (KernelKind kind : {kSweep, kSweepCached, kSweepGrouped, kStream})
+      for (int lr : {1, 2, 4}) {
+        // combinations that have no kernel report AMS_ERR_LAUNCH without touching the device
+        (void)launch_by_ring<FMT, 1>(kind, lr, a, 0, 16, 0, nullptr);
+        (void)launch_by_ring<FMT, 2>(kind, lr, a, 0, 16, 0, nullptr);
+      }
+  }
+  return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
+
+int ams_init(void) {
+  if (const int rc = device_state(); rc != AMS_OK) return rc;
+  int rc = prepare_format<FMT_FP533>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP425>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP45>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP433>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP6>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP5>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP4>();
+  if (rc == AMS_OK) rc = prepare_format<FMT_FP16>();
+  return rc;
+}
 
 int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t* W_out, int64_t N, int64_t K, int scaled,
                 void* stream) {
@@ -1261,6 +1334,7 @@ int ams_dequant_grouped(int fmt, const void* W_packed, const uint16_t* scales, i
   if (!W_packed || !W_out || (scaled && !scales)) return AMS_ERR_NULL;
   if (N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (!aligned16(W_packed)) return AMS_ERR_ALIGN;
+  if (const int rc = device_state(); rc != AMS_OK) return rc;
   int sg_shift = -1, n_sg = 0;  // per-row scales
   if (scale_group != 0) {
     for (int j = 0; j < 20; j++)
@@ -1383,6 +1457,7 @@ int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, in
 int ams_read_probe(const void* buf, size_t bytes, uint32_t* sink, void* stream) {
   if (!buf) return AMS_ERR_NULL;
   if (!aligned16(buf)) return AMS_ERR_ALIGN;
+  if (const int rc = device_state(); rc != AMS_OK) return rc;
   const int64_t n_rec = (int64_t)(bytes / 1024);
   // with nothing to read this is an empty launch of the same shape (the launch floor)
   const unsigned grid = n_rec == 0 ? 1u : (unsigned)std::min<int64_t>(kNumCU, (n_rec + 15) / 16);

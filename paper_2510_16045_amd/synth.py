@@ -37,36 +37,56 @@ QWEN_DOWN_LAYERS = {
 }
 
 
-def _rng(seed_offset: int) -> np.random.Generator:
-    return np.random.default_rng(BASE_SEED + int(seed_offset))
+def _rng(seed_offset: int, chunk: int | None = None) -> np.random.Generator:
+    seed = BASE_SEED + int(seed_offset)
+    return np.random.default_rng(seed if chunk is None else [seed, int(chunk)])
+
+
+def _fill_by_chunks(out: np.ndarray, rows_per_chunk: int, seed_offset: int, draw) -> np.ndarray:
+    """out[r0:r1] = draw(rng of chunk, r1 - r0) for consecutive row chunks.  Every chunk has its own
+    generator, seeded by (seed, chunk index), so the result does not depend on how many threads draw."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    N = out.shape[0]
+    starts = list(range(0, N, rows_per_chunk))
+
+    def one(c):
+        r0 = starts[c]
+        r1 = min(N, r0 + rows_per_chunk)
+        out[r0:r1] = draw(_rng(seed_offset, c), r1 - r0)
+
+    workers = min(16, len(os.sched_getaffinity(0)), len(starts))
+    if workers <= 1:
+        for c in range(len(starts)):
+            one(c)
+    else:
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(one, range(len(starts))))
+    return out
 
 
 def gaussian_weights(N: int, K: int, seed_offset: int = 0, std: float = 0.02) -> np.ndarray:
     """fp16 [N,K] drawn N(0, std) in fp32 then cast."""
-    rng = _rng(seed_offset)
     out = np.empty((N, K), dtype=np.float16)
-    step = max(1, (1 << 24) // max(K, 1))
-    for r0 in range(0, N, step):  # chunked to bound the fp32 temporary
-        r1 = min(N, r0 + step)
-        out[r0:r1] = (rng.standard_normal((r1 - r0, K), dtype=np.float32) * np.float32(std)).astype(np.float16)
-    return out
+    step = max(1, (1 << 22) // max(K, 1))  # chunked: bounds the fp32 temporaries, lets several cores draw
+    return _fill_by_chunks(out, step, seed_offset, lambda rng, n: (rng.standard_normal((n, K), dtype=np.float32) * np.float32(std)).astype(np.float16))
 
 
 def heavy_tail_weights(
     N: int, K: int, seed_offset: int = 0, std: float = 0.02, nu: float = 4.0, p_outlier: float = 1e-3, outlier_gain: float = 20.0
 ) -> np.ndarray:
     """fp16 [N,K]: std * Student-t(nu), a Bernoulli(p_outlier) subset scaled by outlier_gain."""
-    rng = _rng(seed_offset)
-    out = np.empty((N, K), dtype=np.float16)
-    step = max(1, (1 << 23) // max(K, 1))
-    for r0 in range(0, N, step):
-        r1 = min(N, r0 + step)
-        w = rng.standard_t(nu, size=(r1 - r0, K)).astype(np.float32) * np.float32(std)
-        mask = rng.random((r1 - r0, K)) < p_outlier
+
+    def draw(rng, n):
+        w = rng.standard_t(nu, size=(n, K)).astype(np.float32) * np.float32(std)
+        mask = rng.random((n, K), dtype=np.float32) < np.float32(p_outlier)
         w = np.where(mask, w * np.float32(outlier_gain), w)
-        w = np.clip(w, -60000.0, 60000.0)
-        out[r0:r1] = w.astype(np.float16)
-    return out
+        return np.clip(w, -60000.0, 60000.0).astype(np.float16)
+
+    out = np.empty((N, K), dtype=np.float16)
+    step = max(1, (1 << 21) // max(K, 1))
+    return _fill_by_chunks(out, step, seed_offset, draw)
 
 
 def activations(M: int, K: int, seed_offset: int = 0, std: float = 1.0) -> np.ndarray:

@@ -1,0 +1,106 @@
+"""GPU parity on the benchmark configurations at their full sizes, in the launch configuration
+bench.py times: the Llama-70B-shaped layers on heavy-tailed weights with outliers (both paper
+formats, M in {1, 4, 8}), the Llama-8B qkv and down projections, and the Qwen2.5-7B down
+projection of Table 3.  The oracle quantizes a sample of rows (rows are independent: first and
+last strip, a workgroup boundary, a stride through the matrix) and checks those outputs; the
+restored weights of the sampled strips must match bit for bit."""
+
+import numpy as np
+import pytest
+
+import paper_2510_16045_amd as ams
+from oracle import ams_oracle as O
+from paper_2510_16045_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]
+REL_L2_TOL = 1e-3
+MAX_ABS_TOL = 2e-2  # relative to rms(Y_ref)
+
+
+def dev(a: np.ndarray):
+    if a.dtype == np.float16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    return torch.from_numpy(a).cuda()
+
+
+def host16(t) -> np.ndarray:
+    return t.cpu().view(torch.int16).numpy().view(np.float16)
+
+
+def check_linear(y_gpu: np.ndarray, ref: np.ndarray, what=""):
+    y = y_gpu.astype(np.float64)
+    assert np.all(np.isfinite(y)), what
+    rel = np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-300)
+    rms = np.sqrt(np.mean(ref * ref))
+    mx = np.max(np.abs(y - ref)) / max(rms, 1e-300)
+    assert rel <= REL_L2_TOL, f"{what}: rel L2 {rel}"
+    assert mx <= MAX_ABS_TOL, f"{what}: max abs / rms {mx}"
+
+
+def sampled_strips(N: int, stride: int) -> np.ndarray:
+    """Strips of 16 rows: the first, the last, the ones around workgroup 255 / 256 (the grid has 256
+    workgroups and strips are dealt round robin), and every stride-th."""
+    n_strips = -(-N // 16)
+    s = np.r_[0, n_strips - 1, 254:258, np.arange(3, n_strips, stride)]
+    return np.unique(s[s < n_strips])
+
+
+def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False):
+    strips = sampled_strips(N, stride)
+    rows = np.concatenate([np.arange(16 * t, min(N, 16 * t + 16)) for t in strips])
+    ws = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda") if with_workspace else None
+    for fmt, ofmt in PAPER_PAIRS:
+        packed, scales = ams.ams_pack(fmt, W)
+        codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+        assert np.array_equal(scales[rows].view(np.uint16), o_scales.view(np.uint16))
+        wp, sc = dev(packed), dev(scales)
+        # restored weights of the sampled strips, bit for bit (a strip's records are one contiguous
+        # piece of the packed buffer, so a strip is dequantized as a 16-row matrix of its own)
+        strip_bytes = ams.ams_packed_bytes(fmt, 16, K)
+        want = O.dequant_scaled(codes, o_scales, ofmt).view(np.uint16)
+        at = 0
+        for t in strips:
+            n = min(N, 16 * t + 16) - 16 * t
+            got = host16(ams.ams_dequant(fmt, wp[t * strip_bytes : (t + 1) * strip_bytes], sc[16 * t : 16 * t + n], n, K, scaled=True))
+            assert np.array_equal(got.view(np.uint16), want[at : at + n]), f"{ofmt.name} N={N} K={K}: strip {t}"
+            at += n
+        for M in Ms:
+            X = synth.activations(M, K, 500 + M)
+            ref = O.linear(codes, o_scales, X, ofmt)
+            x = dev(X)
+            print(f"{ofmt.name} N={N} K={K} M={M}: {ams.ams_linear_plan(fmt, M, N, K)}", flush=True)
+            y = host16(ams.ams_linear(wp, sc, x, N, fmt))
+            assert np.all(np.isfinite(y.astype(np.float32)))
+            check_linear(y[:, rows], ref, f"{ofmt.name} N={N} K={K} M={M}")
+            if ws is not None:
+                y = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws))
+                check_linear(y[:, rows], ref, f"{ofmt.name} N={N} K={K} M={M} (workspace)")
+        del wp, sc
+
+
+@pytest.mark.parametrize("layer,stride", [("o", 37), ("gate_up", 211), ("down", 61)])
+def test_llama70b_layers_heavy_tail_weights(layer, stride):
+    # Student-t(4) x 0.02 weights, 0.1 % of them x 20: rows with an outlier get a large scale and
+    # mostly subnormal codes, which is what the fp32 scale x 2^14 epilogue has to survive
+    N, K = synth.LLAMA70B_LAYERS[layer]
+    W = synth.heavy_tail_weights(N, K, 700 + len(layer))
+    assert np.abs(W.astype(np.float32)).max() > 2.0  # outliers are there
+    check_shape_against_oracle(N, K, W, (1, 4, 8), stride, with_workspace=layer != "gate_up")
+
+
+@pytest.mark.parametrize("layer,stride", [("qkv", 29), ("o", 23), ("down", 31)])
+def test_llama8b_layers_small_batches(layer, stride):
+    N, K = synth.LLAMA8B_LAYERS[layer]
+    W = synth.gaussian_weights(N, K, 710 + len(layer))
+    check_shape_against_oracle(N, K, W, (1, 2), stride)
+
+
+@pytest.mark.parametrize("model,Ms", [("qwen2.5-7b", (1, 2, 16)), ("qwen3-4b", (1, 32))])
+def test_qwen_down_projections(model, Ms):
+    # MLP-down shapes of Table 3, with and without the split of K
+    N, K = synth.QWEN_DOWN_LAYERS[model]
+    W = synth.gaussian_weights(N, K, 720 + len(model))
+    check_shape_against_oracle(N, K, W, Ms, 23, with_workspace=True)

@@ -459,7 +459,35 @@ def test_linear_is_a_plain_matmul(fmt):
     assert np.array_equal(O.linear(codes, s, E, fmt)[0], D[:, 77])
     # transposed-operand mistake would break this shape check
     assert Y.shape == (3, 40)
-    assert np.allclose(O.fp16_linear(W, X), X.astype(np.float64) @ W.astype(np.float64).T)
+
+
+def test_fp16_linear_is_a_plain_matmul():
+    # the checker of the fp16 baseline kernel, pinned by a scalar triple loop over exactly decoded binary16
+    # inputs (fractions: no floating point in the decode), a one-hot row and a transposed-operand trap
+    from fractions import Fraction
+
+    def half_exact(h):  # IEEE binary16 bit pattern -> exact rational
+        sgn, e, m = h >> 15, (h >> 10) & 31, h & 1023
+        assert e != 31
+        v = Fraction(m, 1 << 24) if e == 0 else Fraction(1024 + m, 1024) * Fraction(2) ** (e - 15)
+        return -v if sgn else v
+
+    W, X = synth.gaussian_weights(7, 33, 12), synth.activations(3, 33, 12)
+    Y = O.fp16_linear(W, X)
+    assert Y.shape == (3, 7) and Y.dtype == np.float64  # [M, N]: a transposed operand would give 7 x 3 or fail
+    Wb, Xb = W.view(np.uint16), X.view(np.uint16)
+    for m in range(3):
+        for n in range(7):
+            exact = sum(half_exact(int(Wb[n, k])) * half_exact(int(Xb[m, k])) for k in range(33))
+            assert abs(Y[m, n] - float(exact)) <= 1e-13 * max(1.0, abs(float(exact))), (m, n)
+    E = np.zeros((1, 33), dtype=np.float16)
+    E[0, 20] = 2.0
+    assert np.array_equal(O.fp16_linear(W, E)[0], 2.0 * W[:, 20].astype(np.float64))
+    # rectangular identity-like weights: Y picks columns of X
+    Wi = np.zeros((4, 33), dtype=np.float16)
+    for n in range(4):
+        Wi[n, 5 * n + 1] = 1.0
+    assert np.array_equal(O.fp16_linear(Wi, X), X[:, [1, 6, 11, 16]].astype(np.float64))
 
 
 def test_quantized_linear_is_close_to_fp16_linear():

@@ -53,6 +53,7 @@ enum {
   AMS_ERR_NONFINITE = -5, /* a weight is inf or NaN */
   AMS_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch (see hipGetLastError) */
   AMS_ERR_DEVICE = -7,    /* the current device is not a gfx950 GPU (returned by every device entry point) */
+  AMS_ERR_SCRATCH = -8,   /* ams_linear_static_ws: the shape is beyond what the library's static scratch holds */
   AMS_ERR_NOMEM = -9      /* a host entry point could not get the memory for its row buffers */
 };
 
@@ -222,6 +223,26 @@ int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* 
                   int64_t K, int fmt, void* workspace, size_t workspace_bytes, void* stream);
 int ams_fp16_linear_ws(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * ams_linear_ws for callers that cannot allocate a workspace (code under HIP graph capture
+ * that may not call hipMalloc, tight serving loops, harnesses that forbid allocation): the
+ * split of K exchanges its partial tiles and arrival counters through a static device array
+ * inside the library (64 KiB + 8 MiB per GPU, held until the process ends) instead of a
+ * caller's buffer.  Same arguments, same kernels and bit-for-bit the same results as
+ * ams_linear_ws with a large enough zero-filled workspace.  Allocates nothing.
+ *   Limit: the workspace this shape's split needs (what ams_linear_workspace_bytes reports)
+ *   must fit the array, i.e. be at most 64 KiB + 8 MiB: true for every shape with up to 16384
+ *   output channels (8192 for M > 16) and for most larger ones, which are not split at all;
+ *   beyond that AMS_ERR_SCRATCH, never a silently different plan (use ams_linear or ams_linear_ws).
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU
+ *   (two streams, two threads) race and must be serialised by the caller.  Each call leaves
+ *   the counters at zero for the next one; the array starts zero-filled when the library is loaded.
+ *   If the first call on a device happens inside a stream capture, call ams_init() before the capture.
+ * Errors: as ams_linear, plus SCRATCH.
+ */
+int ams_linear_static_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
+                         int64_t K, int fmt, void* stream);
 
 /*
  * Measurement aid, not part of the method: a bare streaming read of the first

@@ -63,6 +63,7 @@ def load_library():
     lib.ams_linear.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp]
     lib.ams_fp16_linear.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp]
     lib.ams_linear_workspace_bytes.argtypes = [_int, _int, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
+    lib.ams_linear_static_ws.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp]
     lib.ams_linear_ws.argtypes = [_vp, _vp, _vp, _vp, _int, _i64, _i64, _int, _vp, ctypes.c_size_t, _vp]
     lib.ams_fp16_linear_ws.argtypes = [_vp, _vp, _vp, _int, _i64, _i64, _vp, ctypes.c_size_t, _vp]
     lib.ams_linear_plan.argtypes = [_int, _int, _i64, _i64, _int, ctypes.c_char_p, ctypes.c_size_t]
@@ -294,6 +295,24 @@ def ams_linear_ws(W_packed, scales, X, N: int, fmt: int, workspace, out=None):
         _dev_ptr(workspace, torch.uint8) if workspace is not None else None, workspace.numel() if workspace is not None else 0, _stream()
     )
     _check(rc, "ams_linear_ws")
+    return out
+
+
+def ams_linear_static_ws(W_packed, scales, X, N: int, fmt: int, out=None):
+    """ams_linear_ws with the library's own static scratch as the workspace (allocates nothing)."""
+    import torch
+
+    M, K = X.shape
+    if W_packed.numel() != ams_packed_bytes(fmt, N, K):
+        raise ValueError("packed buffer has the wrong size")
+    if scales.numel() != N:
+        raise ValueError("scales must have N entries")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = load_library().ams_linear_static_ws(
+        _dev_ptr(W_packed, torch.uint8), _dev_ptr(scales, torch.float16), _dev_ptr(X, torch.float16), _dev_ptr(out, torch.float16), M, N, K, fmt, _stream()
+    )
+    _check(rc, "ams_linear_static_ws")
     return out
 
 

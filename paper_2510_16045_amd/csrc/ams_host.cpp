@@ -267,6 +267,7 @@ const char* ams_strerror(int code) {
     case AMS_ERR_NONFINITE: return "weight is inf or NaN";
     case AMS_ERR_LAUNCH: return "kernel launch failed";
     case AMS_ERR_DEVICE: return "current device is not gfx950";
+    case AMS_ERR_SCRATCH: return "problem too large for the library's static scratch (use ams_linear or ams_linear_ws)";
     case AMS_ERR_NOMEM: return "out of host memory";
     default: return "unknown error";
   }

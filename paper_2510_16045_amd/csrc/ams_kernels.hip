@@ -1082,6 +1082,8 @@ size_t split_workspace_bytes(int M, int64_t n_strips, int gk) {
 }
 
 constexpr int kMaxSplit = 8;  // most slices of K choose_split ever takes
+// passed as the workspace by the entry point that uses the library's static scratch instead
+void* const kStaticScratch = (void*)(uintptr_t)1;
 
 // How many slices of K to use when a workspace is available.  A split pays when the strips
 // alone do not fill the compute units evenly (e.g. 320 strips: 2 per workgroup on 160 CUs,
@@ -1116,13 +1118,20 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
 }
 
 // Per-device state, set up once per device with that device current: whether it is the GPU
-// this library is written for.
+// this library is written for, and where this device's copy of the static scratch lives.
 constexpr int kMaxDevices = 64;
 struct DeviceState {
   int status;     // 0 = not looked at yet, 1 = usable, -1 = not a gfx950 with the expected resources
+  void* scratch;  // device address of this device's `scratch` array
 };
 std::mutex g_dev_mu;
 DeviceState g_dev[kMaxDevices];
+
+// Scratch of the entry point that may not allocate (ams_linear_static_ws): the arrival counters
+// and partial tiles of a split of K.  One copy per GPU, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticScratchBytes = ((size_t)64 << 10) + ((size_t)8 << 20);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // AMS_OK when the current device is a gfx950 with the compute units and LDS the launch plans
 // assume; looked up once per device (no allocation, no synchronisation).
@@ -1136,7 +1145,11 @@ int device_state(DeviceState** out = nullptr) {
     d.status = -1;
     if (hipGetDeviceProperties(&prop, dev) == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) == 0 &&
         prop.multiProcessorCount >= 1 && prop.warpSize == 64) {
-      d.status = 1;
+      void* ptr = nullptr;
+      if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) == hipSuccess && ptr) {
+        d.scratch = ptr;
+        d.status = 1;
+      }
     }
     (void)hipGetLastError();  // a failed query must not be reported by the caller's next HIP call
   }
@@ -1211,7 +1224,13 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   if (M < 1 || M > AMS_MAX_M || N <= 0 || K <= 0 || N > (1 << 24) || K > (1 << 24)) return AMS_ERR_SHAPE;
   if (FMT == FMT_FP16 && (K % 8) != 0) return AMS_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(X) || !aligned16(Y) || (scales && !aligned16(scales))) return AMS_ERR_ALIGN;
-  if (const int rc = device_state(); rc != AMS_OK) return rc;
+  DeviceState* dev = nullptr;
+  if (const int rc = device_state(&dev); rc != AMS_OK) return rc;
+  const bool static_ws = workspace == kStaticScratch;
+  if (static_ws) {  // the library's own scratch, this device's copy
+    workspace = dev->scratch;
+    ws_bytes = kStaticScratchBytes;
+  }
   constexpr int REC_K = Fmt<FMT>::REC_K;
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + REC_K - 1) / REC_K);
@@ -1246,7 +1265,10 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   if (workspace && scale_group == 0) {
     if (!aligned16(workspace)) return AMS_ERR_ALIGN;
     gk = choose_split(FMT, M, n_strips, n_rec, REC_K, REC_BYTES);
-    if (split_workspace_bytes(M, n_strips, gk) > ws_bytes) gk = 1;  // too small: no split
+    if (split_workspace_bytes(M, n_strips, gk) > ws_bytes) {
+      if (static_ws) return AMS_ERR_SCRATCH;  // beyond the static array: refused, never silently another plan
+      gk = 1;                                 // a caller's workspace that is too small: no split
+    }
   }
   const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, scale_group != 0, gk);
   if (scale_group != 0 && !wp.ok) return AMS_ERR_SHAPE;
@@ -1320,6 +1342,20 @@ int ams_init(void) {
   if (rc == AMS_OK) rc = prepare_format<FMT_FP4>();
   if (rc == AMS_OK) rc = prepare_format<FMT_FP16>();
   return rc;
+}
+
+int ams_linear_static_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
+                         int64_t K, int fmt, void* stream) {
+  switch (fmt) {
+    case FMT_FP533: return run_linear<FMT_FP533>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP425: return run_linear<FMT_FP425>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP45: return run_linear<FMT_FP45>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP433: return run_linear<FMT_FP433>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP6: return run_linear<FMT_FP6>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP5: return run_linear<FMT_FP5>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+    case FMT_FP4: return run_linear<FMT_FP4>(W_packed, scales, X, Y, M, N, K, stream, 0, kStaticScratch, 0);
+  }
+  return AMS_ERR_FORMAT;
 }
 
 int ams_dequant(int fmt, const void* W_packed, const uint16_t* scales, uint16_t* W_out, int64_t N, int64_t K, int scaled,

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MI355X AMS-Quant weight-only quantized Linear (decode path).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep] [--layers 8b|70b|qwen] [--out FILE]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-sweep] [--no-70b] [--layers 8b|70b|qwen]
 
 One *step* is one pass over the Linear set of one Llama-3-8B decoder layer at decode
 time (fused qkv, o, fused gate/up, down; M = 1) in both AMS formats: eight ams_linear
@@ -12,14 +12,18 @@ step touches each layer's weights once per token and the model never fits a cach
 stdout carries ONE JSON line: whole-step packed-weight GB/s as `value`, per-layer
 figures (us per Linear with percentiles, cache-resident time, GB/s, fraction of the
 8 TB/s HBM peak and of a bare read of the same bytes, speed-up over the in-build fp16
-Linear and the library GEMM) under `layers`, a `roofline` object for the dominant kernel
-and a `cpu_baseline` object (the numpy oracle timed on this host).
-`--sweep` adds the batch sweep M = 1..32 (written to --out, default bench_sweep.json).
+Linear and the library GEMM) under `layers`, a `roofline` object for the dominant kernel,
+a `cpu_baseline` object (the numpy oracle timed on this host) and, unless switched off,
+`batch_sweep` (M = 1..32 on the 8B gate/up and down projections, both formats, plain
+ams_linear and the split of K through the library's static scratch, against the faster of
+the two fp16 baselines) and `llama70b` (the Llama-70B-shaped layers on heavy-tailed weights
+at M = 1, 4, 8).
 """
 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -33,10 +37,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 512 << 20  # a Linear timed alone rotates over copies of its weights worth at least this (2 x the 256 MB last-level cache)
 CLOCK_RAMP_S = 0.5  # untimed load before the warm-up steps, so that an idle GPU's clocks are up
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
-# by what the same counter reads for a 256 MiB device copy (profiles/sweep_kernel_gate_up_fp533_hbm_traffic.md)
-MEASURED_TRAFFIC_BYTES = {("gate_up", "fp5.33-e2m3", 1): (77668 + 56) * 1024}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same counters read for
+# a device copy of known size): kept beside the profile summaries they come from, with the layout version they hold for
+PROFILES_DIR = os.path.join(ROOT, "profiles")
 FMT_NAMES = {0: "fp5.33-e2m3", 1: "fp4.25-e2m2", 2: "fp4.5-e2m2", 3: "fp4.33-e2m2", 4: "fp6-e2m3", 5: "fp5-e2m2", 6: "fp4-e2m1"}
+SWEEP_MS = (1, 2, 4, 8, 16, 32)
 
 
 def parse_args():
@@ -44,15 +49,16 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--layers", default="8b", choices=["8b", "70b", "qwen"])
-    ap.add_argument("--sweep", action="store_true", help="also run the batch sweep M=1..32")
-    ap.add_argument("--out", default=os.path.join(ROOT, "bench_sweep.json"))
-    ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all six formats (the step keeps the paper's two)")
+    ap.add_argument("--layers", default="8b", choices=["8b", "70b", "qwen"], help="layer set of the step and of the per-layer table")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep M=1..32 (gate/up and down of the 8B set)")
+    ap.add_argument("--sweep-all-layers", action="store_true", help="sweep every layer of the set, not only gate/up and down")
+    ap.add_argument("--no-70b", action="store_true", help="skip the Llama-70B-shaped layers at M=1,4,8")
+    ap.add_argument("--out", default=None, help="also write the sweep table to this file")
+    ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all seven formats (the step keeps the paper's two)")
     ap.add_argument("--group-scales", action="store_true", help="also time ams_linear_grouped (one scale per record-sized run of K) per layer")
-    ap.add_argument("--workspace", action="store_true", help="call ams_linear_ws / ams_fp16_linear_ws with a workspace (K may be split over workgroups)")
+    ap.add_argument("--workspace", action="store_true", help="the step and the per-layer table call ams_linear_ws / ams_fp16_linear_ws with a workspace")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-kernel", default=None, metavar="LAYER:FMT:M",
-                   
                     help="only launch one Linear (e.g. gate_up:fp4.25:1, down:fp16:1) a few times, for rocprofv3, and exit")
     ap.add_argument("--copies-mb", type=int, default=1024, help="rotate through at least this many MB of weights per layer set")
     return ap.parse_args()
@@ -65,7 +71,7 @@ def to_dev(a, torch):
 
 
 class Layer:
-    """One Linear: packed copies in both formats + fp16 copies, all resident in HBM."""
+    """One Linear: packed copies in the given formats + fp16 copies, all resident in HBM."""
 
     def __init__(self, name, N, K, W, ams, torch, n_copies, fp16_copies, fmts):
         self.name, self.N, self.K = name, N, K
@@ -82,6 +88,18 @@ class Layer:
         n16 = max(fp16_copies, -(-ROTATE_BYTES // (2 * w.numel())))
         self.w16 = [w] + [w.clone() for _ in range(n16 - 1)]
         self.W = W  # host copy, for the variants packed on demand
+
+
+def build_layers(shapes, maker, seed0, fmts, copies_mb, ams, torch):
+    set_bytes = sum(n * k * 16 // 3 // 8 for n, k in shapes.values())
+    n_copies = max(2, -(-copies_mb * (1 << 20) // set_bytes))
+    fp16_copies = max(2, -(-copies_mb * (1 << 20) // (3 * set_bytes)))
+    layers = []
+    for i, (name, (N, K)) in enumerate(shapes.items()):
+        W = maker(N, K, seed0 + i)
+        layers.append(Layer(name, N, K, W, ams, torch, n_copies, fp16_copies, fmts))
+        del W
+    return layers, n_copies
 
 
 def time_launches(torch, fn, n_launch, warm=2, replays=5, spread=False):
@@ -113,8 +131,20 @@ def time_launches(torch, fn, n_launch, warm=2, replays=5, spread=False):
     return mean, {"p10": round(pick(0.1), 3), "p50": round(pick(0.5), 3), "p90": round(pick(0.9), 3), "replays": replays, "launches_per_replay": n_launch}
 
 
-def cpu_baseline(seconds_hint=15.0):
-    """The oracle's unpack -> dequant -> fp64 matmul, as it stands, on a bounded sample of the gate/up layer."""
+def random_codes(ofmt, N, K, seed):
+    """Seeded random codes whose last bits agree inside every sharing group (input generation only:
+    what the oracle's unpack / dequant / matmul cost does not depend on which codes they are)."""
+    rng = np.random.default_rng(seed)
+    g = ofmt.group
+    rem = rng.integers(0, 1 << (ofmt.code_bits - 1), size=(N, K), dtype=np.uint8)
+    shared = np.repeat(rng.integers(0, 2, size=(N, -(-K // g)), dtype=np.uint8), g, axis=1)[:, :K]
+    return (rem << 1) | shared
+
+
+def cpu_baseline(shapes):
+    """The oracle as it stands (canonical unpack -> dequant -> fp64 matmul, M = 1) timed on this host: the first
+    quarter of the rows of every Linear of the 8B decode step in both formats, one pass (about 10 s of CPU work),
+    plus baseline configurations 1 and 2 in full."""
     from oracle import ams_oracle as O
     from paper_2510_16045_amd import synth
 
@@ -124,33 +154,54 @@ def cpu_baseline(seconds_hint=15.0):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    rows, K = 1024, 4096
-    W = synth.gaussian_weights(rows, K, 3)
-    X = synth.activations(1, K, 3)
-    out = {}
-    total_bytes, total_t = 0, 0.0
-    for fmt in (O.FP533, O.FP425):
-        codes, s, _ = O.ams_quantize(W, fmt)  # offline step, not timed
-        words = O.pack_canonical(codes, fmt)
+
+    def timed(ofmt, codes, s, X, repeats):
+        words = O.pack_canonical(codes, ofmt)  # offline step, not timed
+        K = codes.shape[1]
         best = None
-        for _ in range(3):
+        for _ in range(repeats):
             t0 = time.perf_counter()
-            c = O.unpack_canonical(words, fmt, K)
-            y = O.linear(c, s, X, fmt)
+            c = O.unpack_canonical(words, ofmt, K)
+            y = O.linear(c, s, X, ofmt)
             dt = time.perf_counter() - t0
             best = dt if best is None else min(best, dt)
-        out[fmt.name] = {"us_per_linear_sample": best * 1e6, "GBps": words.nbytes / best / 1e9}
-        total_bytes += words.nbytes
-        total_t += best
-        del y
+            del c, y
+        return words.nbytes, best
+
+    # the step's own workload, both formats; codes are seeded random ones (the oracle's quantizer, the
+    # offline step, would take minutes at this size and is not part of what is timed)
+    total_bytes, total_t, per_layer = 0, 0.0, []
+    for i, (name, (N, K)) in enumerate(shapes.items()):
+        X = synth.activations(1, K, 3)
+        for ofmt in (O.FP533, O.FP425):
+            rows = N // 4  # bounded sample: rows are independent, every layer keeps its own K
+            codes = random_codes(ofmt, rows, K, 77 + i)
+            s = np.full(rows, 0.01, dtype=np.float16)
+            nbytes, t = timed(ofmt, codes, s, X, 1)
+            per_layer.append({"layer": name, "fmt": ofmt.name, "ms": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e9, 4)})
+            total_bytes += nbytes
+            total_t += t
+            del codes
+    # baseline configurations 1 and 2 in full, quantized by the oracle itself (offline, untimed), best of 3
+    configs = {}
+    for label, (W, X), ofmt in (("config1_256x768_fp4.25_m1", synth.config1(), O.FP425), ("config2_4096x4096_fp5.33_m1", synth.config2(), O.FP533)):
+        if W.shape[0] > 1024:  # quantizing 16.7 M weights with the oracle takes ~15 s: random codes, as above
+            codes, s = random_codes(ofmt, *W.shape, 5), np.full(W.shape[0], 0.01, dtype=np.float16)
+        else:
+            codes, s, _ = O.ams_quantize(W, ofmt)
+        nbytes, t = timed(ofmt, codes, s, X, 3)
+        configs[label] = {"us_per_linear": round(t * 1e6, 1), "GBps": round(nbytes / t / 1e9, 4)}
     return {
         "value": total_bytes / total_t / 1e9,
         "unit": "GB/s",
         "cores": threads,
         "host_cores_available": len(os.sched_getaffinity(0)),
         "kind": "oracle",
-        "sample": f"first {rows} rows of the 28672x4096 gate/up layer, M=1, both formats, unpack+dequant+fp64 matmul, best of 3",
-        "per_format": out,
+        "sample": "the first quarter of the rows of each of the eight Linears of the Llama-3-8B decode step (4 layers x FP5.33 + FP4.25, M=1), "
+                  "canonical unpack + dequant + fp64 matmul, one pass each, seeded random codes; `full_configs`: baseline configurations 1 and 2 whole, best of 3",
+        "seconds": round(total_t, 2),
+        "per_layer": per_layer,
+        "full_configs": configs,
     }
 
 
@@ -191,6 +242,53 @@ def profile_kernel(args, shapes, torch, ams, synth):
     print(json.dumps({"profiled": args.profile_kernel, "launches": args.steps}))
 
 
+def measured_traffic(ams, layer, fmt_name, M):
+    """HBM bytes per launch from the tracked counter summaries (profiles/*hbm_traffic*.md carry one line
+    `traffic-json: {...}` each), or None when there is none for this launch or it was measured with another
+    packed layout (major version of the library)."""
+    import glob
+
+    for path in sorted(glob.glob(os.path.join(PROFILES_DIR, "*hbm_traffic*.md"))):
+        try:
+            with open(path) as f:
+                lines = [ln for ln in f if ln.startswith("traffic-json:")]
+            for ln in lines:
+                e = json.loads(ln[len("traffic-json:"):])
+                if e.get("layout_version") == ams.ams_version() // 100 and (e.get("layer"), e.get("fmt"), e.get("M")) == (layer, fmt_name, M):
+                    return int(e["fetch_bytes"]) + int(e["write_bytes"])
+        except (OSError, ValueError, KeyError):
+            continue
+    return None
+
+
+def batch_sweep(layers, fmts, ams, torch, synth, n_launch, ws):
+    """Every layer x M in 1..32 x format: plain ams_linear, the split of K (static scratch), both fp16 baselines."""
+    rows = []
+    for l in layers:
+        for Mb in SWEEP_MS:
+            x = to_dev(synth.activations(Mb, l.K, 9), torch)
+            y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
+            t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % len(l.w16)], x, out=y), n_launch)
+            t16ws = time_launches(torch, lambda i: ams.ams_fp16_linear_ws(l.w16[i % len(l.w16)], x, ws, out=y), n_launch)
+            tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % len(l.w16)].t(), out=y), n_launch)
+            best16 = min(t16, t16ws, tlib)
+            for fmt in fmts:
+                pk, sc = l.packed[fmt], l.scales[fmt]
+                t = time_launches(torch, lambda i: ams.ams_linear(pk[i % len(pk)], sc, x, l.N, fmt, out=y), n_launch)
+                try:
+                    tws = time_launches(torch, lambda i: ams.ams_linear_static_ws(pk[i % len(pk)], sc, x, l.N, fmt, out=y), n_launch)
+                except ams.AmsError:  # shape beyond the static scratch: that entry point does not take it
+                    tws = None
+                tb = t if tws is None else min(t, tws)
+                rows.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
+                             "us_static_ws": None if tws is None else round(tws, 3),
+                             "GBps": round(l.canon[fmt] / t / 1e3, 1), "fp16_us": round(t16, 3), "fp16_ws_us": round(t16ws, 3),
+                             "library_gemm_fp16_us": round(tlib, 3), "speedup_vs_fp16": round(t16 / t, 3),
+                             "speedup_vs_best_fp16": round(best16 / t, 3), "speedup_static_ws_vs_best_fp16": None if tws is None else round(best16 / tws, 3),
+                             "best_speedup_vs_best_fp16": round(best16 / tb, 3)})
+    return rows
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -206,6 +304,7 @@ def main():
         sys.exit(2)
     ams.load_library()
     torch.cuda.set_device(0)
+    ams.ams_init()  # every kernel's LDS limit raised before anything is captured in a graph
 
     shapes = {"8b": synth.LLAMA8B_LAYERS, "70b": synth.LLAMA70B_LAYERS, "qwen": synth.QWEN_DOWN_LAYERS}[args.layers]
     if args.profile_kernel:
@@ -213,27 +312,20 @@ def main():
         return
     maker = synth.heavy_tail_weights if args.layers == "70b" else synth.gaussian_weights
     t_setup = time.perf_counter()
-    set_bytes = sum(n * k * 16 // 3 // 8 for n, k in shapes.values())
-    n_copies = max(2, -(-args.copies_mb * (1 << 20) // set_bytes))
-    fp16_copies = max(2, -(-args.copies_mb * (1 << 20) // (3 * set_bytes)))
     fmts = (ams.FP533, ams.FP425)  # the step: the two formats the paper builds kernels for
     all_fmts = (ams.FP6, ams.FP533, ams.FP5, ams.FP45, ams.FP433, ams.FP425, ams.FP4) if args.all_formats else fmts
-    layers = []
-    for i, (name, (N, K)) in enumerate(shapes.items()):
-        W = maker(N, K, 100 + i)
-        layers.append(Layer(name, N, K, W, ams, torch, n_copies, fp16_copies, all_fmts))
-        del W
-    print(f"# setup {time.perf_counter() - t_setup:.1f}s, {n_copies} packed copies, {fp16_copies} fp16 copies per layer", file=sys.stderr)
+    layers, n_copies = build_layers(shapes, maker, 100, all_fmts, args.copies_mb, ams, torch)
+    print(f"# setup {time.perf_counter() - t_setup:.1f}s, {n_copies} packed copies per layer", file=sys.stderr)
 
-    ws = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda") if args.workspace else None
+    ws = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
 
     def linear(packed, scales, x, N, fmt, out):
-        if ws is None:
+        if not args.workspace:
             return ams.ams_linear(packed, scales, x, N, fmt, out=out)
         return ams.ams_linear_ws(packed, scales, x, N, fmt, ws, out=out)
 
     def fp16_linear(w, x, out):
-        return ams.ams_fp16_linear(w, x, out=out) if ws is None else ams.ams_fp16_linear_ws(w, x, ws, out=out)
+        return ams.ams_fp16_linear(w, x, out=out) if not args.workspace else ams.ams_fp16_linear_ws(w, x, ws, out=out)
 
     M = 1
     xs = {l.name: to_dev(synth.activations(M, l.K, 7), torch) for l in layers}
@@ -272,6 +364,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     step_bytes = sum(l.canon[fmt] for l in layers for fmt in fmts)
     value = step_bytes / (wall / args.steps) / 1e9
+    del graphs
 
     # ---- per-layer figures (each Linear alone, back to back, rotating copies)
     per_layer = []
@@ -320,31 +413,60 @@ def main():
         "bound": "hbm", "kernel": f"sweep_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes,
-        "traffic": MEASURED_TRAFFIC_BYTES.get((dl.name, dom["fmt"], M)) if args.layers == "8b" else None,
+        "traffic": measured_traffic(ams, dl.name, dom["fmt"], M) if args.layers == "8b" else None,
     }
 
     # launch floor: an empty launch of the Linear kernel's shape (256 workgroups x 1024 threads)
     launch_floor = time_launches(torch, lambda i: ams.ams_read_probe(layers[0].packed[fmts[0]][0], 0), n_launch)
 
+    # ---- batch sweep (Table 3's columns): gate/up and down of the 8B set unless told otherwise
     sweep = None
-    if args.sweep:
-        sweep = []
-        for l in layers:
-            for Mb in (1, 2, 4, 8, 16, 32):
-                x = to_dev(synth.activations(Mb, l.K, 9), torch)
-                y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
-                t16 = time_launches(torch, lambda i: fp16_linear(l.w16[i % len(l.w16)], x, y), n_launch)
-                tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % len(l.w16)].t(), out=y), n_launch)
-                for fmt in all_fmts:
-                    t = time_launches(torch, lambda i: linear(l.packed[fmt][i % len(l.packed[fmt])], l.scales[fmt], x, l.N, fmt, y), n_launch)
-                    sweep.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
-                                  "GBps": round(l.canon[fmt] / t / 1e3, 1), "fp16_us": round(t16, 3),
-                                  "library_gemm_fp16_us": round(tlib, 3), "speedup_vs_fp16": round(t16 / t, 3),
-                                  "speedup_vs_best_fp16": round(min(t16, tlib) / t, 3)})
-        with open(args.out, "w") as f:
-            json.dump({"layers": args.layers, "sweep": sweep}, f, indent=1)
+    if not args.no_sweep:
+        sweep_layers = layers if (args.sweep_all_layers or args.layers != "8b") else [l for l in layers if l.name in ("gate_up", "down")]
+        sweep = batch_sweep(sweep_layers, all_fmts, ams, torch, synth, n_launch, ws)
+        if args.out:
+            with open(args.out, "w") as f:
+                json.dump({"layers": args.layers, "sweep": sweep}, f, indent=1)
 
-    cpu = None if args.no_cpu_baseline else cpu_baseline()
+    # ---- the Llama-70B-shaped layers (heavy-tailed weights with outliers) at M = 1, 4, 8
+    llama70b = None
+    if not args.no_70b and args.layers == "8b":
+        del layers, dl, xs, ys
+        l = None
+        gc.collect()
+        torch.cuda.empty_cache()
+        t_setup = time.perf_counter()
+        big, _ = build_layers(synth.LLAMA70B_LAYERS, synth.heavy_tail_weights, 200, fmts, args.copies_mb, ams, torch)
+        print(f"# 70B setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr)
+        llama70b = []
+        for l in big:
+            for Mb in (1, 4, 8):
+                x = to_dev(synth.activations(Mb, l.K, 11), torch)
+                y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
+                nl = 4 * max(len(l.w16), 2)
+                t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % len(l.w16)], x, out=y), nl)
+                tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % len(l.w16)].t(), out=y), nl)
+                for fmt in fmts:
+                    pk, sc = l.packed[fmt], l.scales[fmt]
+                    nl = 4 * len(pk)
+                    t = time_launches(torch, lambda i: ams.ams_linear(pk[i % len(pk)], sc, x, l.N, fmt, out=y), nl)
+                    try:
+                        tws = time_launches(torch, lambda i: ams.ams_linear_static_ws(pk[i % len(pk)], sc, x, l.N, fmt, out=y), nl)
+                    except ams.AmsError:
+                        tws = None
+                    t_read = time_launches(torch, lambda i: ams.ams_read_probe(pk[i % len(pk)]), nl) if Mb == 1 else None
+                    gbps = l.canon[fmt] / t / 1e3
+                    llama70b.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
+                                     "us_static_ws": None if tws is None else round(tws, 3),
+                                     "bare_read_us": None if t_read is None else round(t_read, 3),
+                                     "GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                                     "fp16_us": round(t16, 3), "library_gemm_fp16_us": round(tlib, 3),
+                                     "speedup_vs_fp16": round(t16 / t, 3), "speedup_vs_best_fp16": round(min(t16, tlib) / t, 3)})
+        del big
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(synth.LLAMA8B_LAYERS)
 
     line = {
         "metric": "packed_weight_GBps", "value": round(value, 1), "unit": "GB/s",
@@ -354,7 +476,7 @@ def main():
             "workload": f"Llama-3-8B decode-step Linear set (qkv 6144x4096, o 4096x4096, gate/up 28672x4096, down 4096x14336), M=1, "
                         f"FP5.33-e2m3 + FP4.25-e2m2, weights N(0,0.02), per-row fp16 scales, cold HBM ({n_copies} rotating copies)"
             if args.layers == "8b" else f"{args.layers} layer set, M=1, both formats",
-            "linears_per_step": len(layers) * len(fmts), "packed_bytes_per_step": step_bytes,
+            "linears_per_step": len(shapes) * len(fmts), "packed_bytes_per_step": step_bytes,
             "hbm_peak_GBps": HBM_PEAK_GBPS, "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
             "launch_floor_us": round(launch_floor, 3), "clock_ramp_s": CLOCK_RAMP_S, "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
         },
@@ -362,6 +484,11 @@ def main():
         # the single-Linear configuration of the baseline list (4096x4096, FP5.33-e2m3, M=1) is the `o` layer of this set
         "single_linear_4096x4096_fp533_m1": next(({"us": r["us"], "GBps": r["GBps"], "hbm_frac": r["hbm_frac"], "speedup_vs_fp16": r["speedup_vs_fp16"]}
                                                   for r in per_layer if (r["N"], r["K"], r["fmt"]) == (4096, 4096, FMT_NAMES[0])), None),
+        # baseline configuration 4: us = plain ams_linear, us_static_ws = ams_linear_static_ws (K split over workgroups where it pays);
+        # fp16 side: the in-build kernel without / with a workspace and the library GEMM, the fastest of the three is the denominator
+        "batch_sweep": sweep,
+        # baseline configuration 5: Student-t(4) x 0.02 weights with 0.1 % outliers x 20
+        "llama70b": llama70b,
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",
     }
     print(json.dumps(line))

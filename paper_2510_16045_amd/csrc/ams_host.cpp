@@ -161,14 +161,15 @@ inline int sign_pos(int fmt, int i) {
 }
 inline int mag_pos(int fmt, int i) { return is_e2m3(fmt) ? 8 - 4 * i : 9 - 3 * i; }
 
-// Writes the records of one strip.  codes: 16 rows of K bytes (row pointer NULL = padding row).
-void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], int64_t K, uint8_t* strip_out) {
-  const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
+// Writes the records of strip t of a packed matrix of n_strips strips.  codes: 16 rows of K bytes
+// (row pointer NULL = padding row).  Records beyond K that pad the last side group hold zero codes.
+void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], int64_t K, uint8_t* packed, int64_t n_strips, int64_t t) {
+  const int64_t n_rec = ams::round_up(ams::round_up(K, fi.rec_k) / fi.rec_k, ams::side_group(fi));
   // FP4-e2m1 has no last bit beside its remainder: the nibble is the whole code
   const bool whole = fmt == ams::kFmtFp4;
   const int mag_bits = whole ? fi.code_bits - 1 : fi.code_bits - 2;  // bits of a remainder without its sign
   for (int64_t j = 0; j < n_rec; j++) {
-    uint8_t* rec = strip_out + j * fi.rec_bytes;
+    const ams::RecordPlace rp = ams::record_place(fi, n_strips, t, j);
     for (int l = 0; l < ams::kLanes; l++) {
       const uint8_t* row = rows[l & 15];
       const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
@@ -186,26 +187,27 @@ void pack_strip(int fmt, const FormatInfo& fi, const uint8_t* const rows[16], in
           hw |= lsb << 12;
         words[p.d] |= hw << (16 * p.h);
       }
-      std::memcpy(rec + l * fi.chunk_bytes, words, (size_t)fi.chunk_bytes);
-      for (int b = 0; b < fi.side_bytes; b++) rec[ams::kLanes * fi.chunk_bytes + l * fi.side_bytes + b] = (uint8_t)(side >> (8 * b));
+      std::memcpy(packed + rp.chunks + l * fi.chunk_bytes, words, (size_t)fi.chunk_bytes);
+      // this record's bytes of the lane's side dword (little-endian); the other records of the group write theirs
+      for (int b = 0; b < fi.side_bytes; b++) packed[rp.side + 4 * l + rp.side_shift / 8 + b] = (uint8_t)(side >> (8 * b));
     }
   }
 }
 
-void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* strip_in, int64_t K, uint8_t* const rows[16]) {
+void unpack_strip(int fmt, const FormatInfo& fi, const uint8_t* packed, int64_t n_strips, int64_t t, int64_t K, uint8_t* const rows[16]) {
   const int64_t n_rec = ams::round_up(K, fi.rec_k) / fi.rec_k;
   const bool whole = fmt == ams::kFmtFp4;
   const int mag_bits = whole ? fi.code_bits - 1 : fi.code_bits - 2;
   for (int64_t j = 0; j < n_rec; j++) {
-    const uint8_t* rec = strip_in + j * fi.rec_bytes;
+    const ams::RecordPlace rp = ams::record_place(fi, n_strips, t, j);
     for (int l = 0; l < ams::kLanes; l++) {
       uint8_t* row = rows[l & 15];
       if (!row) continue;
       const int64_t kbase = j * fi.rec_k + (int64_t)(l >> 4) * fi.lane_k;
       uint32_t words[4] = {0, 0, 0, 0};
-      std::memcpy(words, rec + l * fi.chunk_bytes, (size_t)fi.chunk_bytes);
+      std::memcpy(words, packed + rp.chunks + l * fi.chunk_bytes, (size_t)fi.chunk_bytes);
       uint32_t side = 0;
-      for (int b = 0; b < fi.side_bytes; b++) side |= (uint32_t)rec[ams::kLanes * fi.chunk_bytes + l * fi.side_bytes + b] << (8 * b);
+      for (int b = 0; b < fi.side_bytes; b++) side |= (uint32_t)packed[rp.side + 4 * l + rp.side_shift / 8 + b] << (8 * b);
       for (int q = 0; q < fi.lane_k; q++) {
         if (kbase + q >= K) continue;
         const ams::Place p = ams::place(fmt, q);
@@ -287,8 +289,7 @@ int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes) {
   if (int rc = check_shape(fmt, N, K)) return rc;
   if (!bytes) return AMS_ERR_NULL;
   const FormatInfo& fi = *ams::format_info(fmt);
-  *bytes = (size_t)(ams::round_up(N, ams::kStripRows) / ams::kStripRows) * (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) *
-           (size_t)fi.rec_bytes;
+  *bytes = (size_t)ams::packed_bytes(fi, N, K);
   return AMS_OK;
 }
 
@@ -337,7 +338,6 @@ int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N
   const FormatInfo& fi = *ams::format_info(fmt);
   const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax, search};
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
-  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   uint16_t tensor_scale = 0;
   if (per_tensor) {  // Eq. 1 with the maximum over the whole matrix
     double absmax = 0;
@@ -363,7 +363,7 @@ int pack_rows(int fmt, int search, bool per_tensor, const uint16_t* W, int64_t N
       rows[r] = c;
       if (codes_out) std::memcpy(codes_out + n * K, c, (size_t)K);
     }
-    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed, n_strips, t);
   });
   if (!done) return AMS_ERR_NOMEM;
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
@@ -397,7 +397,6 @@ int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W
   const RowQuant rq = {fi.code_bits - 3, fi.group, fi.fmax, search};
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
   const int64_t n_sg = (K + scale_group - 1) / scale_group;
-  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   std::atomic<int> bad{0};
   const bool done = parallel_for(n_strips, [&](int64_t t) {
     std::vector<uint8_t> buf((size_t)ams::kStripRows * K);
@@ -418,7 +417,7 @@ int ams_pack_grouped(int fmt, int search, int64_t scale_group, const uint16_t* W
       rows[r] = c;
       if (codes_out) std::memcpy(codes_out + n * K, c, (size_t)K);
     }
-    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed, n_strips, t);
   });
   if (!done) return AMS_ERR_NOMEM;
   return bad.load() ? AMS_ERR_NONFINITE : AMS_OK;
@@ -429,7 +428,6 @@ int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* pa
   if (!codes || !packed) return AMS_ERR_NULL;
   const FormatInfo& fi = *ams::format_info(fmt);
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
-  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   std::atomic<int> bad{0};
   parallel_for(n_strips, [&](int64_t t) {
     const uint8_t* rows[16];
@@ -443,7 +441,7 @@ int ams_pack_codes(int fmt, const uint8_t* codes, int64_t N, int64_t K, void* pa
           if ((rows[r][k] >> fi.code_bits) || ((rows[r][k] ^ rows[r][k0]) & 1)) bad.store(1);
       }
     }
-    pack_strip(fmt, fi, rows, K, (uint8_t*)packed + t * strip_bytes);
+    pack_strip(fmt, fi, rows, K, (uint8_t*)packed, n_strips, t);
   });
   return bad.load() ? AMS_ERR_SHAPE : AMS_OK;
 }
@@ -453,11 +451,10 @@ int ams_unpack_host(int fmt, const void* packed, int64_t N, int64_t K, uint8_t* 
   if (!codes || !packed) return AMS_ERR_NULL;
   const FormatInfo& fi = *ams::format_info(fmt);
   const int64_t n_strips = ams::round_up(N, ams::kStripRows) / ams::kStripRows;
-  const size_t strip_bytes = (size_t)(ams::round_up(K, fi.rec_k) / fi.rec_k) * fi.rec_bytes;
   parallel_for(n_strips, [&](int64_t t) {
     uint8_t* rows[16];
     for (int r = 0; r < 16; r++) rows[r] = t * 16 + r < N ? codes + (t * 16 + r) * K : nullptr;
-    unpack_strip(fmt, fi, (const uint8_t*)packed + t * strip_bytes, K, rows);
+    unpack_strip(fmt, fi, (const uint8_t*)packed, n_strips, t, K, rows);
   });
   return AMS_OK;
 }

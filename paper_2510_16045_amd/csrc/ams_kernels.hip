@@ -5,11 +5,13 @@
 // Every lane loads its 16-byte chunk of a record with one dwordx4 (a record is one
 // contiguous 1 KiB access per wavefront), restores the fp16 pairs in registers and feeds
 // them as the A operand of v_mfma_f32_16x16x32_f16; the activations are staged in LDS in
-// the operand order the restoration produces.  Two kernels share these pieces:
-// sweep_kernel (the default: one resident round of workgroups, strips dealt round robin,
-// records dealt to the wavefronts one by one, so the grid reads one moving window),
-// stream_kernel (equal contiguous record pieces per wavefront; for shapes whose parked
-// tiles would not fit the sweep's LDS; it takes any shape).
+// the operand order the restoration produces.
+//   column_kernel  the packed formats: a workgroup owns up to 16 neighbouring strips, every
+//                  wavefront stays with one strip and walks K in step with all the others, so
+//                  that the grid as a whole reads one contiguous, moving window of the K-major
+//                  packed matrix; the partial tile of a strip never leaves its wavefront's
+//                  registers until the end.
+//   sweep_kernel / stream_kernel   the fp16 baseline (row-major weights).
 // Partial tiles are combined through LDS, deterministically; only the entry points that take
 // a workspace also split K over workgroups and exchange fp32 tiles through it.
 #include <hip/hip_runtime.h>
@@ -102,11 +104,14 @@ template <int FMT>
 struct Fmt {
   static constexpr int REC_K = ams::kFormats[FMT].rec_k, REC_BYTES = ams::kFormats[FMT].rec_bytes,
                        CHUNK = ams::kFormats[FMT].chunk_bytes, SIDE = ams::kFormats[FMT].side_bytes,
-                       PB = ams::kFormats[FMT].perm_block, N_MFMA = REC_K / 32;
+                       PB = ams::kFormats[FMT].perm_block, N_MFMA = REC_K / 32,
+                       SG = ams::side_group(ams::kFormats[FMT]),       // records per unit (a power of two)
+                       CB = ams::chunk_block_bytes(ams::kFormats[FMT]),  // bytes of one record's lane chunks
+                       UNIT = ams::unit_bytes(ams::kFormats[FMT]);
 };
 template <>
 struct Fmt<FMT_FP16> {
-  static constexpr int REC_K = 128, REC_BYTES = 0, CHUNK = 0, SIDE = 0, PB = 8, N_MFMA = 4;
+  static constexpr int REC_K = 128, REC_BYTES = 0, CHUNK = 0, SIDE = 0, PB = 8, N_MFMA = 4, SG = 1, CB = 0, UNIT = 0;
 };
 
 // Input channel (inside its permutation block) of every operand slot of the block.
@@ -123,21 +128,14 @@ __device__ constexpr int slot_channel(int s) {
   return tab.v[s];
 }
 
-// What one lane holds of one record: the words of its chunk and its side bytes.
+// What one lane holds of one record: the words of its chunk and, for formats with side bits,
+// the lane's side dword of the record's unit (the record's own byte(s) are picked where it is restored).
 template <int SIDE>
 struct SideBits {
   uint32_t t;
 };
 template <>
 struct SideBits<0> {};
-template <>
-struct SideBits<1> {
-  uint8_t t;  // kept narrow: it is widened where it is used, behind that record's own wait
-};
-template <>
-struct SideBits<2> {
-  uint16_t t;
-};
 template <int FMT>
 struct LaneRec : SideBits<Fmt<FMT>::SIDE> {
   uint32_t w[Fmt<FMT>::CHUNK / 4];
@@ -171,43 +169,41 @@ struct LinearArgs {
   unsigned* ws_count;
 };
 
-// One lane's part of the record at `base`: its chunk (one dwordx4, or three dwords that the
-// compiler merges) and its side bytes.
+// One lane's part of a record: its chunk at `chunks` (one dwordx4, or three dwords that the
+// compiler merges) and its dword of the unit's side block at `side`.
 template <int FMT, bool NT>
-__device__ __forceinline__ void load_lane_rec(LaneRec<FMT>& r, const uint8_t* base, int lane) {
+__device__ __forceinline__ void load_lane_rec(LaneRec<FMT>& r, const uint8_t* chunks, const uint8_t* side, int lane) {
   constexpr int CHUNK = Fmt<FMT>::CHUNK, SIDE = Fmt<FMT>::SIDE;
   auto ld = [](auto* p) { return NT ? __builtin_nontemporal_load(p) : *p; };
   if constexpr (CHUNK == 16) {
-    const u4 v = ld((const u4*)(base + lane * 16));
+    const u4 v = ld((const u4*)(chunks + lane * 16));
     r.w[0] = v[0], r.w[1] = v[1], r.w[2] = v[2], r.w[3] = v[3];
   } else {
-    const uint32_t* p = (const uint32_t*)(base + lane * CHUNK);
+    const uint32_t* p = (const uint32_t*)(chunks + lane * CHUNK);
 #pragma unroll
     for (int d = 0; d < CHUNK / 4; d++) r.w[d] = ld(p + d);
   }
-  const uint8_t* side = base + 64 * CHUNK + lane * SIDE;
-  if constexpr (SIDE == 1) r.t = ld(side);
-  if constexpr (SIDE == 2) r.t = ld((const uint16_t*)side);
-  if constexpr (SIDE == 4) r.t = ld((const uint32_t*)side);
+  if constexpr (SIDE != 0) r.t = ld((const uint32_t*)side + lane);
 }
 
 // The MFMA A operands of one record as packed fp16 pairs: o[4u + t] = elements 2t, 2t+1
 // of the lane's row in MFMA u (bit patterns of value * 2^-14).
+// side_shift: first bit of this record's side bits inside the unit's side dword (wave-uniform).
 template <int FMT>
-__device__ __forceinline__ void restore_rec(const LaneRec<FMT>& r, uint32_t (&o)[4 * Fmt<FMT>::N_MFMA]) {
+__device__ __forceinline__ void restore_rec(const LaneRec<FMT>& r, int side_shift, uint32_t (&o)[4 * Fmt<FMT>::N_MFMA]) {
   if constexpr (FMT == FMT_FP533) {
 #pragma unroll
     for (int d = 0; d < 4; d++) restore_fp533(r.w[d], &o[3 * d]);
   } else if constexpr (FMT == FMT_FP6) {
     // side bits: bit 2d + (i-1) = member i of half A of word d, the same + 8 for half B
-    const uint32_t t = r.t;
+    const uint32_t t = r.t >> side_shift;
     const uint32_t spread = (t & 0xFFu) | ((t & 0xFF00u) << 8);
 #pragma unroll
     for (int d = 0; d < 4; d++)
       restore_e2m3(r.w[d], (r.w[d] >> 5) & 0x00800080u, (spread << (7 - 2 * d)) & 0x00800080u, (spread << (6 - 2 * d)) & 0x00800080u,
                    &o[3 * d]);
   } else if constexpr (FMT == FMT_FP425) {
-    const uint32_t spread = spread_side_byte((uint32_t)r.t);
+    const uint32_t spread = spread_side_byte(__builtin_amdgcn_ubfe(r.t, (uint32_t)side_shift, 8u));
 #pragma unroll
     for (int d = 0; d < 4; d++) restore_fp425(r.w[d], pair_bits_e2m2(spread, d), &o[4 * d]);
   } else if constexpr (FMT == FMT_FP4) {
@@ -218,7 +214,7 @@ __device__ __forceinline__ void restore_rec(const LaneRec<FMT>& r, uint32_t (&o)
   } else {
     // FP4.33: one side byte for all words; FP4.5: one per two words; FP5: one per word
     constexpr int WORDS_PER_BYTE = FMT == FMT_FP433 ? 3 : (FMT == FMT_FP45 ? 2 : 1);
-    const uint32_t t = r.t;
+    const uint32_t t = Fmt<FMT>::SIDE == 4 ? r.t : __builtin_amdgcn_ubfe(r.t, (uint32_t)side_shift, (uint32_t)(8 * Fmt<FMT>::SIDE));
     uint32_t sh[4];
 #pragma unroll
     for (int d = 0; d < Fmt<FMT>::CHUNK / 4; d++) {
@@ -252,22 +248,25 @@ __device__ __forceinline__ void load_rec(LaneRec<FMT>& r, const LinearArgs& a, i
       r.w[d] = u4{v[0] & keep, v[1] & keep, v[2] & keep, v[3] & keep};
     }
   } else {
-    const uint8_t* base = a.W + ((size_t)strip * a.n_rec + rec) * Fmt<FMT>::REC_BYTES;
-    load_lane_rec<FMT, NT>(r, base, lane);
+    // unit (rec / SG, strip) of the K-major packed matrix, record rec % SG inside it
+    constexpr int SG = Fmt<FMT>::SG;
+    const uint8_t* unit = a.W + ((size_t)(rec / SG) * a.n_strips + strip) * Fmt<FMT>::UNIT;
+    load_lane_rec<FMT, NT>(r, unit + (rec % SG) * Fmt<FMT>::CB, unit + SG * Fmt<FMT>::CB, lane);
   }
 }
 
 // Multiply one record (16 rows x REC_K) into the accumulators.  x0 / x1 point at this
 // lane's activation row(s) in LDS at the first operand slot of its K-quarter of the record.
+// side_shift: see restore_rec (8 * SIDE * (rec % SG); 0 for formats without side bits).
 template <int FMT, int MT>
-__device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x0, const _Float16* x1, f4 acc[MT]) {
+__device__ __forceinline__ void mac_rec(const LaneRec<FMT>& r, const _Float16* x0, const _Float16* x1, f4 acc[MT], int side_shift = 0) {
   h8 a[Fmt<FMT>::N_MFMA];
   if constexpr (FMT == FMT_FP16) {
 #pragma unroll
     for (int d = 0; d < 4; d++) a[d] = __builtin_bit_cast(h8, r.w[d]);
   } else {
     uint32_t o[4 * Fmt<FMT>::N_MFMA];
-    restore_rec<FMT>(r, o);
+    restore_rec<FMT>(r, side_shift, o);
 #pragma unroll
     for (int u = 0; u < Fmt<FMT>::N_MFMA; u++) a[u] = __builtin_bit_cast(h8, u4{o[4 * u], o[4 * u + 1], o[4 * u + 2], o[4 * u + 3]});
   }
@@ -894,6 +893,209 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   }
 }
 
+// The Linear on packed weights.  A workgroup owns up to 16 neighbouring strips (spw of them,
+// one resident round of workgroups; more strips than 16 x 256 just means more workgroups) and
+// has S / spw wavefronts on each: a wavefront stays with its strip and takes every wps-th
+// record of it, in step with all other wavefronts of the grid.  With the K-major packed layout
+// the grid as a whole then reads one contiguous window of memory that moves through the
+// matrix front to back (measured with bare read kernels under a realistic amount of per-record
+// arithmetic: 10-20 % faster than strips that are read as separate streams).  A strip's
+// partial tile stays in its wavefront's accumulator registers for the whole of K, also across
+// the phases K is walked in when the activations M x K do not fit in LDS; at the end the wps
+// tiles of a strip are added in wave order through LDS (deterministic, no atomics), scaled,
+// converted and stored.  Each wave keeps LR records in flight beside the one it is restoring.
+template <int FMT, int MT, bool NT, bool GS>
+__global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, LR = 2, RS = LR + 1;
+  asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wps));
+  const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int S = nthr >> 6;
+  // workgroup = (position g along N, slice gk of K); without a split the grid is all along N
+  const int G = a.gn;
+  const int gk = a.gk > 1 ? (int)(blockIdx.x / (unsigned)G) : 0;
+  const int g = (int)blockIdx.x - gk * G;
+  const int s_first = g * a.spw;                      // this workgroup's strips: s_first .. s_first + ns - 1
+  const int ns = min(a.spw, a.n_strips - s_first);    // >= 1
+  const int wps = a.wps;                              // wavefronts per strip
+  const int wj = (int)((unsigned)wave / (unsigned)wps), wk = wave - wj * wps;  // this wave: strip wj of the workgroup, lane wk of its K deal
+  const bool has_strip = wj < ns;
+  const int strip = s_first + (has_strip ? wj : 0);
+  // records [rec_lo, rec_hi) of every strip are this workgroup's slice of K
+  const int rec_lo = a.gk > 1 ? (int)((unsigned)(gk * a.n_rec) / (unsigned)a.gk) : 0;
+  const int rec_hi = a.gk > 1 ? (int)((unsigned)((gk + 1) * a.n_rec) / (unsigned)a.gk) : a.n_rec;
+  const int RC = a.rc;  // records per strip in one phase of K
+  const int mc = min(a.M, 16);  // activation rows of an MFMA tile that exist
+  _Float16* xs = (_Float16*)smem;
+  f4* parts = (f4*)(smem + (size_t)a.x_region * 2);  // [spw][wps][MT][4 K-quarters][mc]
+  const int m_lo = lane & 15, kq = lane >> 4;
+  const int lane_off = (REC_K / 4) * kq;
+  // lanes whose activation row does not exist read row 0: they only feed output columns never stored
+  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
+  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
+  const int part_f4 = MT * 4 * mc;  // f4 per parked tile
+
+  const bool vec_x = (a.K & 7) == 0;
+  const int total_units = a.M << a.x_shift;
+  const int units_per_pass = nthr * XUnit<FMT>::XU;
+  const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
+  const int chunk_k = RC * REC_K;
+  // Scales of the strip this wave finishes (wave w finishes strip w of the workgroup): requested first, kept as raw
+  // bits until the epilogue.  (With one scale per run of input channels, GS, the scales travel with the records.)
+  ScaleBits scale0_bits = {{0x3C00, 0x3C00, 0x3C00, 0x3C00}};
+  if constexpr (!GS) scale0_bits = load_scale_bits<FMT>(a, min(s_first + min(wave, ns - 1), a.n_strips - 1), lane);
+  __builtin_amdgcn_sched_barrier(0);
+
+  f4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; i++) acc[i] = f4{0, 0, 0, 0};
+
+  // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
+  for (int rec_base = rec_lo; rec_base < rec_hi; rec_base += RC) {
+    const int n_rec = min(RC, rec_hi - rec_base);                                    // records per strip in this phase
+    const int cnt = (has_strip && wk < n_rec) ? (n_rec - wk + wps - 1) / wps : 0;  // records of this wave
+    if (rec_base > rec_lo) __syncthreads();  // everyone is done with the previous phase's activations
+    const int k0 = rec_base * REC_K;
+
+    // Activations: units beyond the first pass (large M) and unaligned rows are staged by loops
+    // that run to completion; the first pass is only requested here and stored behind the
+    // head of the weight stream, so both are in flight together.
+    XRegs<FMT> xr;
+    if (vec_x) {
+      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
+        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
+        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
+      }
+    } else {
+      stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
+    }
+    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // LR records are in flight while a record is being restored: the ring has one slot more,
+    // and a step first requests the record LR places ahead into the slot freed by the step
+    // before, then works on its own.  The request cursor stops at the wave's last record (a
+    // wave without records requests, and ignores, the phase's first record of its strip).
+    struct Slot {
+      LaneRec<FMT> r;
+      us4 gs;  // GS: the scales of this lane's four output channels for the record's run
+    };
+    Slot ring[RS];
+    int pr = rec_base + (cnt > 0 ? wk : 0);                       // record the next request fetches
+    const int pr_last = rec_base + (cnt > 0 ? wk + (cnt - 1) * wps : 0);
+    auto request = [&](Slot& slot) {
+      load_rec<FMT, NT>(slot.r, a, strip, pr, lane);
+      if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
+        slot.gs = *(const us4*)(a.scales + ((size_t)strip * a.n_sg + (pr >> a.sg_shift)) * 16 + 4 * kq);
+      pr = min(pr + wps, pr_last);
+    };
+#pragma unroll
+    for (int q = 0; q < LR; q++) {
+      request(ring[q]);
+      __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
+    }
+    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+    __syncthreads();
+
+    // One record: request the one LR ahead, restore, multiply, move on by wps records.
+    int cr = wk;  // record being multiplied, relative to the phase
+    auto step = [&](Slot& slot, Slot& free_slot) {
+      request(free_slot);
+      __builtin_amdgcn_sched_barrier(0);
+      const int side_shift = 8 * Fmt<FMT>::SIDE * ((rec_base + cr) & (SG - 1));
+      if constexpr (GS) {  // the record's own tile, times its run's scales (Eq. 2), then into the sum
+        f4 t[MT];
+#pragma unroll
+        for (int i = 0; i < MT; i++) t[i] = f4{0, 0, 0, 0};
+        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, t, side_shift);
+        f4 sc;
+#pragma unroll
+        for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)slot.gs[r]);
+#pragma unroll
+        for (int i = 0; i < MT; i++) acc[i] += t[i] * sc;
+      } else {
+        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc, side_shift);
+      }
+      cr += wps;
+    };
+    int i = 0;
+    for (; i + RS <= cnt; i += RS) {
+#pragma unroll
+      for (int q = 0; q < RS; q++) {
+        step(ring[q], ring[(q + LR) % RS]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < RS - 1; q++)
+      if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
+  }
+
+  // Finish the strips, one per wave: the wps tiles of a strip added in wave order.
+  if (has_strip && m_lo < mc) {
+    f4* t = parts + (size_t)(wj * wps + wk) * part_f4 + kq * mc + m_lo;
+#pragma unroll
+    for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
+  }
+  __syncthreads();
+  for (int j = wave; j < ns; j += S) {
+    f4 sum[MT];
+#pragma unroll
+    for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+    if (m_lo < mc) {
+      const f4* t0 = parts + (size_t)j * wps * part_f4 + kq * mc + m_lo;
+      for (int w = 0; w < wps; w++) {
+#pragma unroll
+        for (int t = 0; t < MT; t++) sum[t] += t0[(size_t)w * part_f4 + t * 4 * mc];
+      }
+    }
+    const int out_strip = s_first + j;
+    if (a.gk > 1) {
+      // K is split over gk workgroups: every one leaves its partial tile in the workspace and
+      // counts itself in; the one that arrives last adds all gk tiles in slice order (so the
+      // result does not depend on who was last), finishes the strip and clears the counter
+      // for the next call.  Nobody waits for anybody.
+      // The tiles travel as device-scope relaxed atomic stores and loads (they go to the level
+      // of the memory system all compute units share).  What orders them: the wave waits until
+      // every one of its tile stores has been acknowledged (s_waitcnt vmcnt(0): on this target
+      // stores count in vmcnt) before it counts itself in, and the last arriver's tile loads are
+      // issued only after its own count has come back (the branch below depends on it).  A
+      // device-scope fence would instead write back and invalidate the whole L2, which costs
+      // more than the Linear itself.
+      float* wt = (float*)(a.ws_tiles + ((size_t)gk * a.n_strips + out_strip) * MT * 64 + lane);
+#pragma unroll
+      for (int t = 0; t < MT; t++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) __hip_atomic_store(wt + t * 256 + r, sum[t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // all tile stores of this wave acknowledged; the compiler moves no memory access across either statement
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      unsigned before = 0;
+      if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + out_strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      before = __builtin_amdgcn_readfirstlane(before);
+      if (before != (unsigned)a.gk - 1) continue;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the count has returned; the tile loads below are issued after it
+#pragma unroll
+      for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+      for (int q = 0; q < a.gk; q++) {
+        const float* rt = (const float*)(a.ws_tiles + ((size_t)q * a.n_strips + out_strip) * MT * 64 + lane);
+#pragma unroll
+        for (int t = 0; t < MT; t++)
+#pragma unroll
+          for (int r = 0; r < 4; r++) sum[t][r] += __hip_atomic_load(rt + t * 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lane == 0) __hip_atomic_store(a.ws_count + out_strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    f4 sc;
+    if constexpr (GS)
+      sc = f4{kTwo14, kTwo14, kTwo14, kTwo14};
+    else
+      sc = j == wave ? scales_from_bits(scale0_bits, kTwo14) : load_scales<FMT>(a, out_strip, lane);
+    store_tile_scaled<MT>(sum, sc, a, out_strip, lane);
+  }
+}
+
 // Restore a whole packed matrix to row-major fp16: one wavefront per record.
 template <int FMT>
 __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const uint16_t* scales, uint16_t* out, int N, int K,
@@ -902,9 +1104,11 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
   const int64_t rec_id = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (rec_id >= total_recs) return;
   const int strip = (int)(rec_id / n_rec), rec = (int)(rec_id - (int64_t)strip * n_rec);
-  const uint8_t* base = W + (size_t)rec_id * Fmt<FMT>::REC_BYTES;
+  constexpr int SG = Fmt<FMT>::SG;
+  const int64_t n_strips = (N + 15) / 16;
+  const uint8_t* unit = W + ((size_t)(rec / SG) * n_strips + strip) * Fmt<FMT>::UNIT;
   LaneRec<FMT> r;
-  load_lane_rec<FMT, false>(r, base, lane);
+  load_lane_rec<FMT, false>(r, unit + (rec % SG) * Fmt<FMT>::CB, unit + SG * Fmt<FMT>::CB, lane);
   const int n = strip * 16 + (lane & 15);
   if (n >= N) return;
   float mul = kTwo14;
@@ -920,7 +1124,7 @@ __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* W, const ui
     }
   };
   uint32_t o[4 * Fmt<FMT>::N_MFMA];
-  restore_rec<FMT>(r, o);
+  restore_rec<FMT>(r, 8 * Fmt<FMT>::SIDE * (rec % SG), o);
   constexpr int PB = Fmt<FMT>::PB;
 #pragma unroll
   for (int m = 0; m < 4 * Fmt<FMT>::N_MFMA; m++) {
@@ -1072,6 +1276,47 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
   return p;
 }
 
+struct ColumnPlan {
+  int S, spw, grid, gn, gk, wps, rc, n_phase, x_shift, x_stride, x_region;
+  size_t lds;
+};
+
+// Launch shape of the packed formats' kernel: 16 wavefronts per workgroup, up to 16 neighbouring
+// strips per workgroup (one resident round of workgroups where the matrix allows it), 16 / strips
+// wavefronts on each strip; LDS holds the activations of one phase of K, in as few phases as fit,
+// and one tile per wavefront for the final sum.  Every shape the entry points accept gets a plan.
+// gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
+ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1) {
+  ColumnPlan p;
+  const int mt = M > 16 ? 2 : 1;
+  const int mc = std::min(M, 16);
+  p.gk = gk;
+  p.S = 16;
+  const int n_rec = (n_rec_all + gk - 1) / gk;  // records of the longest slice
+  const int wg_along_n = kNumCU / gk;
+  p.spw = (int)std::min<int64_t>(16, (n_strips + wg_along_n - 1) / wg_along_n);
+  p.gn = (int)((n_strips + p.spw - 1) / p.spw);
+  p.grid = p.gn * gk;
+  p.wps = p.S / p.spw;
+  const size_t parts = (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
+  for (int n_phase = 1;; n_phase++) {
+    const int rc = (n_rec + n_phase - 1) / n_phase;
+    const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
+    const size_t lds = (size_t)M * x_stride * 2 + parts;
+    if (lds > (size_t)kLdsMaxBytes && rc > 1) continue;  // one record per phase always fits (32 rows x 136 halfs)
+    p.rc = rc;
+    p.n_phase = (n_rec + rc - 1) / rc;
+    p.x_stride = x_stride;
+    p.x_region = M * x_stride;
+    p.lds = lds;
+    const int units = rc * rec_k / x_unit(fmt);
+    p.x_shift = 0;
+    while ((1 << p.x_shift) < units) p.x_shift++;
+    break;
+  }
+  return p;
+}
+
 // Workspace of a split in gk slices: per-strip arrival counters, then the partial tiles.  The
 // counter area has one size for every shape, so that a workspace that is reused for another
 // shape never finds old tile data where it expects counters at zero.
@@ -1099,8 +1344,18 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
   double best_cost = 0;
   for (int gk = 1; gk <= kMaxSplit; gk *= 2) {
     if (gk > 1 && (n_rec / gk < 8 || n_strips > kSplitMaxStrips)) break;
-    const SweepPlan p = make_sweep_plan(fmt, M, n_strips, n_rec, rec_k, false, gk);
-    int spw = p.spw, rc = p.rc;
+    int spw, rc;
+    double rounds = 1.0;  // the packed formats' workgroups take at most 16 strips: more of them means more rounds
+    SweepPlan p;
+    p.ok = true;
+    if (fmt != FMT_FP16) {
+      const ColumnPlan cp = make_column_plan(fmt, M, n_strips, n_rec, rec_k, gk);
+      spw = cp.spw, rc = cp.rc;
+      rounds = std::max(1.0, (double)cp.grid / kNumCU);
+    } else {
+      p = make_sweep_plan(fmt, M, n_strips, n_rec, rec_k, false, gk);
+      spw = p.spw, rc = p.rc;
+    }
     if (!p.ok) {
       if (gk > 1) continue;
       // without a split the shape would go to the contiguous-piece kernel: price that one
@@ -1112,6 +1367,7 @@ int choose_split(int fmt, int M, int64_t n_strips, int n_rec, int rec_k, int rec
     const double n_phase = std::max(1.0, slice / rc);
     double cost = spw * slice * rec_bytes + 0.5 * M * slice * rec_k * 2 + 8192.0 * (n_phase - 1);
     if (gk > 1) cost += 49152.0 + 2048.0 * gk * spw * (M > 16 ? 2 : 1);
+    cost *= rounds;
     if (best_cost == 0 || cost < best_cost) best = gk, best_cost = cost;
   }
   return best;
@@ -1188,33 +1444,33 @@ int launch(Kern kern, const LinearArgs& a, unsigned grid, int S, size_t lds, hip
   return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
-enum KernelKind { kSweep, kSweepCached, kSweepGrouped, kStream };
+enum KernelKind { kSweep, kStream };
 
-template <int FMT, int MT>
-int launch_by_ring(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+// The fp16 baseline's kernels by ring depth and wave grouping.
+template <int MT>
+int launch_fp16(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  constexpr int FMT = FMT_FP16;
   const bool groups = a.wps != S;  // wave groups per strip: their own instantiation, the common case stays lean
-  if (kind == kSweepGrouped) {
-    if constexpr (FMT != FMT_FP16)
-      return groups ? launch(sweep_kernel<FMT, MT, 2, true, true, true>, a, grid, S, lds, st)
-                    : launch(sweep_kernel<FMT, MT, 2, true, true, false>, a, grid, S, lds, st);
-  } else if (kind == kSweep || kind == kSweepCached) {
-    if constexpr (FMT == FMT_FP16) {
-      if (lr == 1)
-        return groups ? launch(sweep_kernel<FMT, MT, 1, false, false, true>, a, grid, S, lds, st)
-                      : launch(sweep_kernel<FMT, MT, 1, false, false, false>, a, grid, S, lds, st);
-      if (lr == 2 && !groups) return launch(sweep_kernel<FMT, MT, 2, false, false, false>, a, grid, S, lds, st);
-    } else if (lr == 2) {
-      if (groups) return launch(sweep_kernel<FMT, MT, 2, true, false, true>, a, grid, S, lds, st);
-      return kind == kSweep ? launch(sweep_kernel<FMT, MT, 2, true>, a, grid, S, lds, st)
-                            : launch(sweep_kernel<FMT, MT, 2, false>, a, grid, S, lds, st);
-    }
-  } else if (kind == kStream) {
+  if (kind == kSweep) {
+    if (lr == 1)
+      return groups ? launch(sweep_kernel<FMT, MT, 1, false, false, true>, a, grid, S, lds, st)
+                    : launch(sweep_kernel<FMT, MT, 1, false, false, false>, a, grid, S, lds, st);
+    if (lr == 2 && !groups) return launch(sweep_kernel<FMT, MT, 2, false, false, false>, a, grid, S, lds, st);
+  } else {
     switch (lr) {
       case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
       case 2: return launch(stream_kernel<FMT, MT, 2>, a, grid, S, lds, st);
     }
   }
   return AMS_ERR_LAUNCH;
+}
+
+// The packed formats' kernel: nt = non-temporal weight loads, gs = one scale per run of input channels.
+template <int FMT, int MT>
+int launch_column(bool nt, bool gs, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  if (gs) return launch(column_kernel<FMT, MT, true, true>, a, grid, S, lds, st);
+  return nt ? launch(column_kernel<FMT, MT, true, false>, a, grid, S, lds, st)
+            : launch(column_kernel<FMT, MT, false, false>, a, grid, S, lds, st);
 }
 
 template <int FMT>
@@ -1260,6 +1516,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.wps = 1;
   a.ws_tiles = nullptr;
   a.ws_count = nullptr;
+  a.red_slots = 0;
+  a.piece_q = a.piece_r = 0;
   constexpr int REC_BYTES = FMT == FMT_FP16 ? 4096 : Fmt<FMT>::REC_BYTES;
   int gk = 1;
   if (workspace && scale_group == 0) {
@@ -1270,61 +1528,87 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
       gk = 1;                                 // a caller's workspace that is too small: no split
     }
   }
-  const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, scale_group != 0, gk);
-  if (scale_group != 0 && !wp.ok) return AMS_ERR_SHAPE;
-  if (wp.ok) {
-    a.gn = wp.gn;
-    a.gk = wp.gk;
-    a.wps = wp.wps;
-    if (wp.gk > 1) {
+  auto use_split = [&](int plan_gk) {
+    if (plan_gk > 1) {
       a.ws_count = (unsigned*)workspace;
       a.ws_tiles = (f4*)((uint8_t*)workspace + kSplitCounterBytes);
     }
-    a.x_stride = wp.x_stride;
-    a.x_region = wp.x_region;
-    a.x_shift = wp.x_shift;
-    a.spw = wp.spw;
-    a.red_slots = 0;
-    a.piece_q = a.piece_r = 0;
-    a.rc = wp.rc;
+  };
+  if constexpr (FMT != FMT_FP16) {
+    const ColumnPlan cp = make_column_plan(FMT, M, n_strips, n_rec, REC_K, gk);
+    a.gn = cp.gn;
+    a.gk = cp.gk;
+    a.wps = cp.wps;
+    use_split(cp.gk);
+    a.x_stride = cp.x_stride;
+    a.x_region = cp.x_region;
+    a.x_shift = cp.x_shift;
+    a.spw = cp.spw;
+    a.rc = cp.rc;
     // Non-temporal loads for everything but tiny matrices.  Measured with every call reading weights that are not
     // in any cache (a model's layers in turn): equal or up to 5 % faster than ordinary loads at every size; ordinary
     // loads only win when the same few megabytes are read again call after call.
-    const KernelKind kind = scale_group != 0 ? kSweepGrouped
-                            : n_strips * n_rec * (int64_t)Fmt<FMT>::REC_BYTES < (2ll << 20) ? kSweepCached : kSweep;
-    return M <= 16 ? launch_by_ring<FMT, 1>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st)
-                   : launch_by_ring<FMT, 2>(kind, wp.lr, a, wp.grid, wp.S, wp.lds, st);
+    const bool nt = n_strips * n_rec * (int64_t)REC_BYTES >= (2ll << 20);
+    return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, a, cp.grid, cp.S, cp.lds, st)
+                   : launch_column<FMT, 2>(nt, scale_group != 0, a, cp.grid, cp.S, cp.lds, st);
+  } else {
+    const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, false, gk);
+    if (wp.ok) {
+      a.gn = wp.gn;
+      a.gk = wp.gk;
+      a.wps = wp.wps;
+      use_split(wp.gk);
+      a.x_stride = wp.x_stride;
+      a.x_region = wp.x_region;
+      a.x_shift = wp.x_shift;
+      a.spw = wp.spw;
+      a.rc = wp.rc;
+      return M <= 16 ? launch_fp16<1>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st) : launch_fp16<2>(kSweep, wp.lr, a, wp.grid, wp.S, wp.lds, st);
+    }
+    const StreamPlan sp = make_stream_plan(FMT, M, n_strips, n_rec, REC_K);
+    if (sp.ok) {
+      a.x_stride = sp.x_stride;
+      a.x_region = sp.x_region;
+      a.x_shift = sp.x_shift;
+      a.spw = sp.spw;
+      a.red_slots = sp.red_slots;
+      a.piece_q = (int)(((int64_t)sp.spw * sp.rc) / sp.S);
+      a.piece_r = (int)(((int64_t)sp.spw * sp.rc) % sp.S);
+      a.rc = sp.rc;
+      return M <= 16 ? launch_fp16<1>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st) : launch_fp16<2>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st);
+    }
+    return AMS_ERR_SHAPE;  // not reached: the contiguous-piece plan accepts every shape the checks above let through
   }
-  const StreamPlan sp = make_stream_plan(FMT, M, n_strips, n_rec, REC_K);
-  if (sp.ok) {
-    a.x_stride = sp.x_stride;
-    a.x_region = sp.x_region;
-    a.x_shift = sp.x_shift;
-    a.spw = sp.spw;
-    a.red_slots = sp.red_slots;
-    a.piece_q = (int)(((int64_t)sp.spw * sp.rc) / sp.S);
-    a.piece_r = (int)(((int64_t)sp.spw * sp.rc) % sp.S);
-    a.rc = sp.rc;
-    return M <= 16 ? launch_by_ring<FMT, 1>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st)
-                   : launch_by_ring<FMT, 2>(kStream, sp.lr, a, sp.grid, sp.S, sp.lds, st);
-  }
-  return AMS_ERR_SHAPE;  // not reached: the contiguous-piece plan accepts every shape the checks above let through
 }
 
 // Raise the LDS limit of every Linear kernel of one weight format on the current device.
 template <int FMT>
 int prepare_format() {
   LinearArgs a = {};
-  for (int groups = 0; groups < 2; groups++) {
-    a.wps = groups ? 8 : 16;
-    for (KernelKind kind : {kSweep, kSweepCached, kSweepGrouped, kStream})
-      for (int lr : {1, 2, 4}) {
-        // combinations that have no kernel report AMS_ERR_LAUNCH without touching the device
-        (void)launch_by_ring<FMT, 1>(kind, lr, a, 0, 16, 0, nullptr);
-        (void)launch_by_ring<FMT, 2>(kind, lr, a, 0, 16, 0, nullptr);
+  bool ok = true;
+  if constexpr (FMT != FMT_FP16) {
+    for (int nt = 0; nt < 2; nt++)
+      for (int gs = 0; gs < 2; gs++) {
+        if (gs && !nt) continue;
+        ok &= launch_column<FMT, 1>(nt, gs, a, 0, 16, 0, nullptr) == AMS_OK;
+        ok &= launch_column<FMT, 2>(nt, gs, a, 0, 16, 0, nullptr) == AMS_OK;
       }
+  } else {
+    for (int groups = 0; groups < 2; groups++) {
+      a.wps = groups ? 8 : 16;
+      ok &= launch_fp16<1>(kSweep, 1, a, 0, 16, 0, nullptr) == AMS_OK;
+      ok &= launch_fp16<2>(kSweep, 1, a, 0, 16, 0, nullptr) == AMS_OK;
+    }
+    a.wps = 16;
+    ok &= launch_fp16<1>(kSweep, 2, a, 0, 16, 0, nullptr) == AMS_OK;
+    ok &= launch_fp16<2>(kSweep, 2, a, 0, 16, 0, nullptr) == AMS_OK;
+    for (int lr : {2, 4}) {
+      ok &= launch_fp16<1>(kStream, lr, a, 0, 16, 0, nullptr) == AMS_OK;
+      ok &= launch_fp16<2>(kStream, lr, a, 0, 16, 0, nullptr) == AMS_OK;
+    }
   }
-  return hipGetLastError() == hipSuccess ? AMS_OK : AMS_ERR_LAUNCH;
+  (void)hipGetLastError();
+  return ok ? AMS_OK : AMS_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -1454,6 +1738,12 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
   const int64_t n_strips = (N + 15) / 16;
   const int n_rec = (int)((K + rec_k - 1) / rec_k);
   const int gk = with_workspace ? choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes) : 1;
+  if (f != FMT_FP16) {
+    const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk);
+    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu", cp.grid, cp.spw,
+             cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds);
+    return AMS_OK;
+  }
   const SweepPlan wp = make_sweep_plan(f, M, n_strips, n_rec, rec_k, false, gk);
   if (wp.ok) {
     const int slice = (n_rec + gk - 1) / gk;

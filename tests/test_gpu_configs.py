@@ -57,16 +57,13 @@ def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False):
         codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
         assert np.array_equal(scales[rows].view(np.uint16), o_scales.view(np.uint16))
         wp, sc = dev(packed), dev(scales)
-        # restored weights of the sampled strips, bit for bit (a strip's records are one contiguous
-        # piece of the packed buffer, so a strip is dequantized as a 16-row matrix of its own)
-        strip_bytes = ams.ams_packed_bytes(fmt, 16, K)
+        # restored weights of the sampled rows, bit for bit (the whole matrix is restored on the GPU, the
+        # sampled rows are gathered there and compared on the host)
+        full = ams.ams_dequant(fmt, wp, sc, N, K, scaled=True)
+        got = host16(full[torch.from_numpy(rows).cuda()].contiguous())
+        del full
         want = O.dequant_scaled(codes, o_scales, ofmt).view(np.uint16)
-        at = 0
-        for t in strips:
-            n = min(N, 16 * t + 16) - 16 * t
-            got = host16(ams.ams_dequant(fmt, wp[t * strip_bytes : (t + 1) * strip_bytes], sc[16 * t : 16 * t + n], n, K, scaled=True))
-            assert np.array_equal(got.view(np.uint16), want[at : at + n]), f"{ofmt.name} N={N} K={K}: strip {t}"
-            at += n
+        assert np.array_equal(got.view(np.uint16), want), f"{ofmt.name} N={N} K={K}: restored weights"
         for M in Ms:
             X = synth.activations(M, K, 500 + M)
             ref = O.linear(codes, o_scales, X, ofmt)

@@ -203,7 +203,7 @@ def test_linear_full_size_sampled_rows(fmt, ofmt):
 @pytest.mark.parametrize(
     "N,K,Ms",
     [
-        (28672, 4096, (1, 4, 16, 32)),  # Llama-8B gate/up: 7 strips per workgroup; M=16 walks K in phases, M=32 takes the contiguous-piece kernel
+        (28672, 4096, (1, 4, 16, 32)),  # Llama-8B gate/up: 7 strips per workgroup, two wavefronts on each; M=32 walks K in phases
         (4200, 14336, (1, 8)),  # long K, workgroups with 2 strips and with 1; M=8 walks K in phases
         (8200, 1000, (1, 32)),  # ragged everything, 3 strips per workgroup, two MFMA row tiles
     ],
@@ -305,7 +305,7 @@ def test_linear_random_large_shapes_sampled_rows():
             y = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws) if use_ws else ams.ams_linear(wp, sc, x, N, fmt)).astype(np.float64)
             assert np.all(np.isfinite(y)), what
             check_linear(y[:, rows].astype(np.float16), ref, what + (" (workspace)" if use_ws else ""))
-    assert kinds == {"sweep", "stream"}  # the draw reaches both kernels
+    assert kinds == {"column"}  # every packed format takes the one kernel, whatever the shape
 
 
 def test_linear_random_shapes_all_entry_points():

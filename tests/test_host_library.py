@@ -17,6 +17,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PAPER_PAIRS = [(ams.FP533, O.FP533), (ams.FP425, O.FP425)]  # the two formats the paper builds kernels for
 PAIRS = PAPER_PAIRS + [(ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3), (ams.FP5, O.FP5_E2M2), (ams.FP4, O.FP4_E2M1)]
 REC = {ams.FP533: (96, 1024), ams.FP425: (128, 1088), ams.FP45: (128, 1152), ams.FP433: (96, 832), ams.FP6: (96, 1152), ams.FP5: (128, 1280), ams.FP4: (128, 1024)}
+# records of a strip that share one block of side dwords (K is padded to whole groups of them)
+SIDE_GROUP = {ams.FP533: 1, ams.FP425: 4, ams.FP45: 2, ams.FP433: 4, ams.FP6: 2, ams.FP5: 1, ams.FP4: 1}
 
 
 def test_library_exports_every_declared_symbol():
@@ -34,17 +36,18 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
-@pytest.mark.parametrize("N,K", [(1, 1), (16, 96), (17, 100), (5, 13), (256, 768), (33, 1000)])
+@pytest.mark.parametrize("N,K", [(1, 1), (16, 96), (17, 100), (5, 13), (256, 768), (33, 1000), (32, 1536), (4096, 4096)])
 def test_sizes(fmt, ofmt, N, K):
     if (fmt, ofmt) in PAPER_PAIRS:
         assert ams.ams_canonical_bytes(fmt, N, K) == O.canonical_packed_bytes(ofmt, N, K)
     rec_k, rec_b = REC[fmt]
-    want = (-(-N // 16)) * (-(-K // rec_k)) * rec_b
+    sg = SIDE_GROUP[fmt]
+    want = (-(-N // 16)) * (-(-(-(-K // rec_k)) // sg) * sg) * rec_b
     assert ams.ams_packed_bytes(fmt, N, K) == want
     # a record holds exactly bits-per-weight * 16 * rec_k bits
     assert rec_b * 8 == round(ofmt.bits_per_weight * 16 * rec_k)
     # without padding the gfx950 layout takes exactly the bytes of the densest packing
-    if N % 16 == 0 and K % rec_k == 0:
+    if N % 16 == 0 and K % (rec_k * sg) == 0:
         assert ams.ams_packed_bytes(fmt, N, K) == ams.ams_canonical_bytes(fmt, N, K)
         assert ams.ams_packed_bytes(fmt, N, K) * 8 == round(ofmt.bits_per_weight * N * K)
 
@@ -173,7 +176,7 @@ def test_degenerate_rows_and_errors(fmt, ofmt):
 
 
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
-@pytest.mark.parametrize("N,K", [(16, 96), (16, 128), (19, 131), (1, 1), (48, 777)])
+@pytest.mark.parametrize("N,K", [(16, 96), (16, 128), (16, 192), (16, 256), (16, 384), (16, 512), (19, 131), (1, 1), (48, 777)])
 def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
     rng = np.random.default_rng(N * 1000 + K)
     g = ofmt.group
@@ -183,7 +186,7 @@ def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
     packed = ams.ams_pack_codes(fmt, codes)
     assert np.array_equal(ams.ams_unpack_host(fmt, packed, N, K), codes)
     # every stored bit matters: flipping any bit of a record that holds no padding changes a code
-    if N % 16 == 0 and K % REC[fmt][0] == 0 and N * K <= 16 * 128:
+    if N % 16 == 0 and K % (REC[fmt][0] * SIDE_GROUP[fmt]) == 0 and N * K <= 16 * 512:
         for byte in range(0, packed.size, 7):
             for bit in range(8):
                 p2 = packed.copy()
@@ -200,6 +203,40 @@ def test_layout_roundtrip_random_codes(fmt, ofmt, N, K):
             ams.ams_pack_codes(fmt, bad)
 
 
+@pytest.mark.parametrize("fmt,ofmt", PAIRS)
+def test_layout_is_k_major_in_units_of_side_groups(fmt, ofmt):
+    # record r of strip s lives in unit (r // sg, s) at ((r // sg) * n_strips + s) * unit_bytes: its lane chunks in
+    # chunk block r % sg of the unit, its last bits (if the format keeps them beside the chunks) in the unit's side dwords
+    rec_k, rec_b = REC[fmt]
+    sg = SIDE_GROUP[fmt]
+    n_strips, n_rec = 3, 2 * sg + 1
+    N, K = 16 * n_strips - 5, rec_k * n_rec - 7
+    unit = rec_b * sg
+    chunk_block = 64 * {ams.FP433: 12}.get(fmt, 16)
+    side_bytes = (rec_b - chunk_block) // 64
+    assert ams.ams_packed_bytes(fmt, N, K) == (-(-n_rec // sg)) * n_strips * unit
+    full = (1 << ofmt.code_bits) - 1  # all bits set: sign, largest magnitude, last bit 1
+    for strip in range(n_strips):
+        for rec in range(n_rec):
+            codes = np.zeros((N, K), dtype=np.uint8)
+            k0 = rec * rec_k
+            codes[16 * strip + 2, k0 : min(K, k0 + rec_k)] = full  # one whole row of one record
+            packed = ams.ams_pack_codes(fmt, codes)
+            nz = np.flatnonzero(packed)
+            base = ((rec // sg) * n_strips + strip) * unit
+            lo, hi = base + (rec % sg) * chunk_block, base + (rec % sg + 1) * chunk_block
+            in_chunks = (nz >= lo) & (nz < hi)
+            in_side = (nz >= base + sg * chunk_block) & (nz < base + unit)
+            assert np.all(in_chunks | in_side), (strip, rec)
+            assert in_chunks.any()
+            if side_bytes:
+                # the record's own byte(s) of the lanes' side dwords, nothing else
+                side_at = nz[in_side] - (base + sg * chunk_block)
+                assert side_at.size and np.all((side_at % 4) // side_bytes == rec % sg), (strip, rec)
+            else:
+                assert not in_side.any()
+
+
 def test_padding_is_zero_and_layout_is_deterministic():
     W = synth.gaussian_weights(5, 50, 3)
     for fmt, _ in PAIRS:
@@ -211,20 +248,25 @@ def test_padding_is_zero_and_layout_is_deterministic():
         assert not z.any()
 
 
-def test_launch_plans_cover_both_kernels_and_the_split():
-    # host logic only: which kernel a shape is sent to (the GPU tests run these very shapes)
+def test_launch_plans_cover_the_kernels_and_the_split():
+    # host logic only: which kernel and launch shape a problem gets (the GPU tests run these very shapes)
     plan = lambda *a, **k: dict(kv.split("=") for kv in ams.ams_linear_plan(*a, **k).split()[1:])
     kind = lambda *a, **k: ams.ams_linear_plan(*a, **k).split()[0]
-    assert kind(ams.FP533, 1, 28672, 4096) == "sweep"
+    assert kind(ams.FP533, 1, 28672, 4096) == "column"
     p = plan(ams.FP533, 1, 28672, 4096)
-    assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves_per_strip"], p["phases"]) == ("256", "7", "1", "16", "1")
-    assert int(plan(ams.FP533, 16, 28672, 4096)["waves_per_strip"]) < 16  # parked tiles would not fit otherwise
-    assert kind(ams.FP533, 32, 28672, 4096) == "sweep" and int(plan(ams.FP533, 32, 28672, 4096)["phases"]) <= 4
-    assert kind(ams.FP533, 32, 57344, 8192) == "stream"  # many parked tiles and more than four phases
+    assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves_per_strip"], p["phases"]) == ("256", "7", "1", "2", "1")
+    p = plan(ams.FP425, 1, 4096, 14336)  # one strip per workgroup: all 16 wavefronts on it
+    assert (p["grid"], p["strips_per_wg"], p["waves_per_strip"], p["phases"]) == ("256", "1", "16", "1")
+    p = plan(ams.FP533, 1, 57344, 8192)
+    assert (p["grid"], p["strips_per_wg"], p["waves_per_strip"]) == ("256", "14", "1")
+    assert plan(ams.FP533, 1, 128256, 4096)["strips_per_wg"] == "16"  # more strips than 16 x 256: more workgroups
+    assert int(plan(ams.FP533, 1, 128256, 4096)["grid"]) == -(-(-(-128256 // 16)) // 16)
+    assert kind(ams.FP533, 32, 57344, 8192) == "column" and int(plan(ams.FP533, 32, 57344, 8192)["phases"]) > 1
     assert int(plan(ams.FP425, 8, 4096, 14336)["phases"]) > 1
     assert plan(ams.FP425, 8, 4096, 14336, with_workspace=True)["k_slices"] == "4"
     assert plan(ams.FP425, 1, 4096, 14336, with_workspace=True)["k_slices"] == "1"
     assert kind(-1, 1, 4096, 4096) == "sweep"
+    assert kind(-1, 32, 57344, 8192) == "stream"  # the baseline with many parked tiles and more than two phases
     for fmt, _ in PAIRS:
         for M in (1, 7, 16, 17, 32):
             for N, K in [(1, 1), (16, 5), (37, 1000), (100000, 64), (64, 100000), (1 << 20, 96)]:
@@ -299,13 +341,15 @@ def test_launch_plans_random_shapes_stay_inside_the_machine():
         for ws in (False, True):
             text = ams.ams_linear_plan(fmt, M, N, K, with_workspace=ws)
             kind, kv = text.split()[0], dict(x.split("=") for x in text.split()[1:])
-            assert kind in ("sweep", "stream"), text
+            assert kind == ("column" if fmt >= 0 else kind) and kind in ("column", "sweep", "stream"), text
             assert 0 < int(kv["lds"]) <= 160 * 1024, text
             assert 1 <= int(kv["waves"]) <= 16 and int(kv["phases"]) >= 1 and int(kv["grid"]) >= 1, text
             n_strips = -(-N // 16)
             assert int(kv["strips_per_wg"]) * int(kv["grid"]) >= n_strips * int(kv["k_slices"]) or kind == "stream", text
             if kind == "sweep":
                 assert 16 % int(kv["waves_per_strip"]) == 0 or int(kv["waves_per_strip"]) == int(kv["waves"]), text
+            if kind == "column":
+                assert int(kv["strips_per_wg"]) <= 16 and int(kv["waves_per_strip"]) == 16 // int(kv["strips_per_wg"]), text
             if not ws:
                 assert kv["k_slices"] == "1", text
             need = ams.ams_linear_workspace_bytes(fmt, M, N, K)

@@ -72,10 +72,10 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     # a shape whose split of K wants more than the static array holds; the size check comes before
     # anything is launched, so the pointers of a small problem are enough
     limit = (64 << 10) + (8 << 20)
-    assert ams.ams_linear_workspace_bytes(ams.FP533, 17, 20000, 28672) > limit
-    assert lib.ams_linear_static_ws(p(wp), p(sc), p(x), p(y), 17, 20000, 28672, 0, None) == -8  # AMS_ERR_SCRATCH
-    assert ams.ams_linear_workspace_bytes(ams.FP425, 8, 100000, 28672) > limit
-    assert lib.ams_linear_static_ws(p(wp), p(sc), p(x), p(y), 8, 100000, 28672, 1, None) == -8
+    assert ams.ams_linear_workspace_bytes(ams.FP533, 32, 36000, 14336) > limit
+    assert lib.ams_linear_static_ws(p(wp), p(sc), p(x), p(y), 32, 36000, 14336, 0, None) == -8  # AMS_ERR_SCRATCH
+    assert ams.ams_linear_workspace_bytes(ams.FP425, 17, 36000, 28672) > limit
+    assert lib.ams_linear_static_ws(p(wp), p(sc), p(x), p(y), 17, 36000, 28672, 1, None) == -8
     assert b"scratch" in lib.ams_strerror(-8)
     assert lib.ams_linear_static_ws(p(wp), p(sc), p(x), p(y), 1, 16, 96, 9, None) == -1
     assert lib.ams_linear_static_ws(None, p(sc), p(x), p(y), 1, 16, 96, 0, None) == -3

@@ -18,6 +18,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -171,7 +172,7 @@ struct LinearArgs {
 
 // One lane's part of a record: its chunk at `chunks` (one dwordx4, or three dwords that the
 // compiler merges) and its dword of the unit's side block at `side`.
-template <int FMT, bool NT>
+template <int FMT, bool NT, bool WITH_SIDE = true>
 __device__ __forceinline__ void load_lane_rec(LaneRec<FMT>& r, const uint8_t* chunks, const uint8_t* side, int lane) {
   constexpr int CHUNK = Fmt<FMT>::CHUNK, SIDE = Fmt<FMT>::SIDE;
   auto ld = [](auto* p) { return NT ? __builtin_nontemporal_load(p) : *p; };
@@ -183,7 +184,8 @@ __device__ __forceinline__ void load_lane_rec(LaneRec<FMT>& r, const uint8_t* ch
 #pragma unroll
     for (int d = 0; d < CHUNK / 4; d++) r.w[d] = ld(p + d);
   }
-  if constexpr (SIDE != 0) r.t = ld((const uint32_t*)side + lane);
+  // WITH_SIDE = false: the caller keeps the group's side dword elsewhere
+  if constexpr (SIDE != 0 && WITH_SIDE) r.t = ld((const uint32_t*)side + lane);
 }
 
 // The MFMA A operands of one record as packed fp16 pairs: o[4u + t] = elements 2t, 2t+1
@@ -904,7 +906,10 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
 // the phases K is walked in when the activations M x K do not fit in LDS; at the end the wps
 // tiles of a strip are added in wave order through LDS (deterministic, no atomics), scaled,
 // converted and stored.  Each wave keeps LR records in flight beside the one it is restoring.
-template <int FMT, int MT, bool NT, bool GS>
+// QD (formats with side bits): the records are dealt to a strip's wavefronts in whole side groups,
+// so that a group's side dword is loaded once per group and not once per record; used where the
+// groups of a phase divide evenly enough among the wavefronts (the host decides).
+template <int FMT, int MT, bool NT, bool GS, bool QD = false>
 __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, LR = 2, RS = LR + 1;
@@ -974,63 +979,112 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
     __builtin_amdgcn_sched_barrier(0);
 
-    // LR records are in flight while a record is being restored: the ring has one slot more,
-    // and a step first requests the record LR places ahead into the slot freed by the step
-    // before, then works on its own.  The request cursor stops at the wave's last record (a
-    // wave without records requests, and ignores, the phase's first record of its strip).
-    struct Slot {
-      LaneRec<FMT> r;
-      us4 gs;  // GS: the scales of this lane's four output channels for the record's run
-    };
-    Slot ring[RS];
-    int pr = rec_base + (cnt > 0 ? wk : 0);                       // record the next request fetches
-    const int pr_last = rec_base + (cnt > 0 ? wk + (cnt - 1) * wps : 0);
-    auto request = [&](Slot& slot) {
-      load_rec<FMT, NT>(slot.r, a, strip, pr, lane);
-      if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
-        slot.gs = *(const us4*)(a.scales + ((size_t)strip * a.n_sg + (pr >> a.sg_shift)) * 16 + 4 * kq);
-      pr = min(pr + wps, pr_last);
-    };
-#pragma unroll
-    for (int q = 0; q < LR; q++) {
-      request(ring[q]);
-      __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
-    }
-    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
-    __syncthreads();
-
-    // One record: request the one LR ahead, restore, multiply, move on by wps records.
-    int cr = wk;  // record being multiplied, relative to the phase
-    auto step = [&](Slot& slot, Slot& free_slot) {
-      request(free_slot);
+    if constexpr (QD) {
+      // Side groups dealt whole: the wave's records are its groups wk, wk + wps, ... of the phase, member by
+      // member.  Two groups per unrolled round, so that the ring slot of a record (its number mod 4), the side
+      // register of its group (the group's number mod 2) and its place in the side dword are all fixed in the
+      // code.  LR = 2 records ahead as above; a group's side dword is requested with its first record.
+      constexpr int UN = 2 * SG;
+      const int n_grp = (n_rec + SG - 1) / SG;  // the phase starts on a group boundary; a last group may run into the padding records
+      const int cnt_g = (has_strip && wk < n_grp) ? (n_grp - wk + wps - 1) / wps : 0;
+      const int total_e = cnt_g * SG, e_last = max(total_e - 1, 0);
+      const int g_first = cnt_g > 0 ? wk : 0;
+      LaneRec<FMT> ring[4];
+      uint32_t side[2] = {0, 0};
+      // e-th record of this wave (clamped to its last): group g_first + (e / SG) * wps, member e % SG
+      auto request = [&](int e, LaneRec<FMT>& slot, uint32_t& side_reg, bool with_side) {
+        e = min(e, e_last);
+        const int grp = rec_base / SG + g_first + (e / SG) * wps;
+        const uint8_t* unit = a.W + ((size_t)grp * a.n_strips + strip) * Fmt<FMT>::UNIT;
+        load_lane_rec<FMT, NT, false>(slot, unit + (e % SG) * Fmt<FMT>::CB, nullptr, lane);
+        if (with_side) {
+          const uint32_t* sp = (const uint32_t*)(unit + SG * Fmt<FMT>::CB) + lane;
+          side_reg = NT ? __builtin_nontemporal_load(sp) : *sp;
+        }
+      };
+      request(0, ring[0], side[0], true);
       __builtin_amdgcn_sched_barrier(0);
-      const int side_shift = 8 * Fmt<FMT>::SIDE * ((rec_base + cr) & (SG - 1));
-      if constexpr (GS) {  // the record's own tile, times its run's scales (Eq. 2), then into the sum
-        f4 t[MT];
+      request(1, ring[1], side[(1 / SG) & 1], 1 % SG == 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+      __syncthreads();
+
+      int rel = g_first * SG;  // first record of the group being multiplied, relative to the phase
+      auto round_of = [&](int b, auto n_steps) {
 #pragma unroll
-        for (int i = 0; i < MT; i++) t[i] = f4{0, 0, 0, 0};
-        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, t, side_shift);
-        f4 sc;
-#pragma unroll
-        for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)slot.gs[r]);
-#pragma unroll
-        for (int i = 0; i < MT; i++) acc[i] += t[i] * sc;
-      } else {
-        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc, side_shift);
+        for (int u = 0; u < decltype(n_steps)::value; u++) {
+          request(b + u + LR, ring[(u + LR) & 3], side[((u + LR) / SG) & 1], (u + LR) % SG == 0);
+          __builtin_amdgcn_sched_barrier(0);
+          LaneRec<FMT> cur = ring[u & 3];
+          cur.t = side[(u / SG) & 1];
+          const int kk = (rel + u % SG) * REC_K;
+          mac_rec<FMT, MT>(cur, x0 + kk, x1 + kk, acc, 8 * Fmt<FMT>::SIDE * (u % SG));
+          if (u % SG == SG - 1) rel += wps * SG;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      int b = 0;
+      for (; b + UN <= total_e; b += UN) round_of(b, std::integral_constant<int, UN>{});
+      if (b < total_e) round_of(b, std::integral_constant<int, SG>{});  // an odd last group
+    } else {
+      // LR records are in flight while a record is being restored: the ring has one slot more,
+      // and a step first requests the record LR places ahead into the slot freed by the step
+      // before, then works on its own.  The request cursor stops at the wave's last record (a
+      // wave without records requests, and ignores, the phase's first record of its strip).
+      struct Slot {
+        LaneRec<FMT> r;
+        us4 gs;  // GS: the scales of this lane's four output channels for the record's run
+      };
+      Slot ring[RS];
+      int pr = rec_base + (cnt > 0 ? wk : 0);                       // record the next request fetches
+      const int pr_last = rec_base + (cnt > 0 ? wk + (cnt - 1) * wps : 0);
+      auto request = [&](Slot& slot) {
+        load_rec<FMT, NT>(slot.r, a, strip, pr, lane);
+        if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
+          slot.gs = *(const us4*)(a.scales + ((size_t)strip * a.n_sg + (pr >> a.sg_shift)) * 16 + 4 * kq);
+        pr = min(pr + wps, pr_last);
+      };
+  #pragma unroll
+      for (int q = 0; q < LR; q++) {
+        request(ring[q]);
+        __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
       }
-      cr += wps;
-    };
-    int i = 0;
-    for (; i + RS <= cnt; i += RS) {
-#pragma unroll
-      for (int q = 0; q < RS; q++) {
-        step(ring[q], ring[(q + LR) % RS]);
+      if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+      __syncthreads();
+
+      // One record: request the one LR ahead, restore, multiply, move on by wps records.
+      int cr = wk;  // record being multiplied, relative to the phase
+      auto step = [&](Slot& slot, Slot& free_slot) {
+        request(free_slot);
         __builtin_amdgcn_sched_barrier(0);
+        const int side_shift = 8 * Fmt<FMT>::SIDE * ((rec_base + cr) & (SG - 1));
+        if constexpr (GS) {  // the record's own tile, times its run's scales (Eq. 2), then into the sum
+          f4 t[MT];
+  #pragma unroll
+          for (int i = 0; i < MT; i++) t[i] = f4{0, 0, 0, 0};
+          mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, t, side_shift);
+          f4 sc;
+  #pragma unroll
+          for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)slot.gs[r]);
+  #pragma unroll
+          for (int i = 0; i < MT; i++) acc[i] += t[i] * sc;
+        } else {
+          mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc, side_shift);
+        }
+        cr += wps;
+      };
+      int i = 0;
+      for (; i + RS <= cnt; i += RS) {
+  #pragma unroll
+        for (int q = 0; q < RS; q++) {
+          step(ring[q], ring[(q + LR) % RS]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
+  #pragma unroll
+      for (int q = 0; q < RS - 1; q++)
+        if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
     }
-#pragma unroll
-    for (int q = 0; q < RS - 1; q++)
-      if (i + q < cnt) step(ring[q], ring[(q + LR) % RS]);
   }
 
   // Finish the strips, one per wave: the wps tiles of a strip added in wave order.
@@ -1278,6 +1332,7 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
 
 struct ColumnPlan {
   int S, spw, grid, gn, gk, wps, rc, n_phase, x_shift, x_stride, x_region;
+  bool qd;  // records dealt in whole side groups
   size_t lds;
 };
 
@@ -1286,8 +1341,10 @@ struct ColumnPlan {
 // wavefronts on each strip; LDS holds the activations of one phase of K, in as few phases as fit,
 // and one tile per wavefront for the final sum.  Every shape the entry points accept gets a plan.
 // gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
-ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1) {
+// allow_qd: the caller's variant can deal whole side groups (not with one scale per run of input channels).
+ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1, bool allow_qd = true) {
   ColumnPlan p;
+  const int sg = ams::side_group(ams::kFormats[fmt]);
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
   p.gk = gk;
@@ -1299,11 +1356,22 @@ ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int
   p.grid = p.gn * gk;
   p.wps = p.S / p.spw;
   const size_t parts = (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
+  // Whole side groups per wavefront where that divides the work evenly enough: the phases then start on group
+  // boundaries, and every wavefront of a strip must get (nearly) the same number of groups.
+  p.qd = false;
   for (int n_phase = 1;; n_phase++) {
-    const int rc = (n_rec + n_phase - 1) / n_phase;
+    int rc = (n_rec + n_phase - 1) / n_phase;
+    bool qd = allow_qd && sg > 1 && gk == 1;
+    if (qd) {
+      const int rcq = (rc + sg - 1) / sg * sg;
+      const int groups = rcq / sg, per_wave = (groups + p.wps - 1) / p.wps;
+      qd = (size_t)M * (rcq * rec_k + 8) * 2 + parts <= (size_t)kLdsMaxBytes && groups >= p.wps && per_wave * p.wps * 100 <= groups * 103;
+      if (qd) rc = rcq;
+    }
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
     const size_t lds = (size_t)M * x_stride * 2 + parts;
     if (lds > (size_t)kLdsMaxBytes && rc > 1) continue;  // one record per phase always fits (32 rows x 136 halfs)
+    p.qd = qd;
     p.rc = rc;
     p.n_phase = (n_rec + rc - 1) / rc;
     p.x_stride = x_stride;
@@ -1467,8 +1535,13 @@ int launch_fp16(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int
 
 // The packed formats' kernel: nt = non-temporal weight loads, gs = one scale per run of input channels.
 template <int FMT, int MT>
-int launch_column(bool nt, bool gs, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+int launch_column(bool nt, bool gs, bool qd, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
   if (gs) return launch(column_kernel<FMT, MT, true, true>, a, grid, S, lds, st);
+  if constexpr (Fmt<FMT>::SG > 1) {
+    if (qd)
+      return nt ? launch(column_kernel<FMT, MT, true, false, true>, a, grid, S, lds, st)
+                : launch(column_kernel<FMT, MT, false, false, true>, a, grid, S, lds, st);
+  }
   return nt ? launch(column_kernel<FMT, MT, true, false>, a, grid, S, lds, st)
             : launch(column_kernel<FMT, MT, false, false>, a, grid, S, lds, st);
 }
@@ -1535,7 +1608,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     }
   };
   if constexpr (FMT != FMT_FP16) {
-    const ColumnPlan cp = make_column_plan(FMT, M, n_strips, n_rec, REC_K, gk);
+    const ColumnPlan cp = make_column_plan(FMT, M, n_strips, n_rec, REC_K, gk, scale_group == 0);
     a.gn = cp.gn;
     a.gk = cp.gk;
     a.wps = cp.wps;
@@ -1549,8 +1622,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     // in any cache (a model's layers in turn): equal or up to 5 % faster than ordinary loads at every size; ordinary
     // loads only win when the same few megabytes are read again call after call.
     const bool nt = n_strips * n_rec * (int64_t)REC_BYTES >= (2ll << 20);
-    return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, a, cp.grid, cp.S, cp.lds, st)
-                   : launch_column<FMT, 2>(nt, scale_group != 0, a, cp.grid, cp.S, cp.lds, st);
+    return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st)
+                   : launch_column<FMT, 2>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st);
   } else {
     const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, false, gk);
     if (wp.ok) {
@@ -1588,11 +1661,12 @@ int prepare_format() {
   bool ok = true;
   if constexpr (FMT != FMT_FP16) {
     for (int nt = 0; nt < 2; nt++)
-      for (int gs = 0; gs < 2; gs++) {
-        if (gs && !nt) continue;
-        ok &= launch_column<FMT, 1>(nt, gs, a, 0, 16, 0, nullptr) == AMS_OK;
-        ok &= launch_column<FMT, 2>(nt, gs, a, 0, 16, 0, nullptr) == AMS_OK;
-      }
+      for (int gs = 0; gs < 2; gs++)
+        for (int qd = 0; qd < 2; qd++) {
+          if (gs && (!nt || qd)) continue;
+          ok &= launch_column<FMT, 1>(nt, gs, qd, a, 0, 16, 0, nullptr) == AMS_OK;
+          ok &= launch_column<FMT, 2>(nt, gs, qd, a, 0, 16, 0, nullptr) == AMS_OK;
+        }
   } else {
     for (int groups = 0; groups < 2; groups++) {
       a.wps = groups ? 8 : 16;
@@ -1740,8 +1814,8 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
   const int gk = with_workspace ? choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes) : 1;
   if (f != FMT_FP16) {
     const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk);
-    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu", cp.grid, cp.spw,
-             cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds);
+    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d", cp.grid,
+             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0);
     return AMS_OK;
   }
   const SweepPlan wp = make_sweep_plan(f, M, n_strips, n_rec, rec_k, false, gk);

@@ -249,6 +249,30 @@ def test_linear_activations_in_several_phases(fmt, ofmt, N, K, Ms):
         check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"N={N} K={K} M={M}")
 
 
+@pytest.mark.parametrize("fmt,ofmt", [(ams.FP425, O.FP425), (ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3)])
+def test_linear_records_dealt_in_whole_side_groups(fmt, ofmt):
+    # formats that keep last bits beside the chunks: where the side groups of a strip divide evenly among its
+    # wavefronts they are dealt whole (one side dword per group); an odd number of groups per wavefront, a last
+    # group that runs into the padding records, several phases of K at M = 32
+    sg = {ams.FP425: 4, ams.FP45: 2, ams.FP433: 4, ams.FP6: 2}[fmt]
+    N = 20496  # 1281 strips: 6 per workgroup, two wavefronts on each
+    rows = np.unique(np.r_[0:16, N - 16 : N, np.arange(9, N, 211), 16 * 95 : 16 * 97])
+    # six groups per strip (three per wavefront, the last one partly padding) in one phase; 32 / sg groups in two phases at M = 32
+    for K, Ms in ((REC_K[fmt] * sg * 6 - 5, (1, 5)), (REC_K[fmt] * 32 - 5, (32,))):
+        W = synth.gaussian_weights(N, K, 87)
+        packed, scales = ams.ams_pack(fmt, W)
+        wp, sc = dev(packed), dev(scales)
+        codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+        for M in Ms:
+            plan = ams.ams_linear_plan(fmt, M, N, K)
+            assert "side_groups=1" in plan and "waves_per_strip=2" in plan, plan
+            assert ("phases=1 " in plan) == (M < 32), plan
+            X = synth.activations(M, K, 88 + M)
+            y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt)).astype(np.float64)
+            assert np.all(np.isfinite(y))
+            check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt), f"side groups fmt {ofmt.name} K={K} M={M}")
+
+
 def test_linear_70b_gate_up_sampled_rows():
     # the largest benchmark shape (57344 x 8192, 14 strips per workgroup, 313 MB packed), FP5.33
     N, K = synth.LLAMA70B_LAYERS["gate_up"]

@@ -165,7 +165,8 @@ struct LinearArgs {
   // split of K over gk workgroups per strip (sweep kernel with a workspace): workgroups along N,
   // slices of K, per-slice partial tiles [gk][strip][MT][64] f4, per-strip arrival counters
   int gn, gk;
-  int wps;  // sweep kernel: wavefronts that share a strip (the workgroup works on S / wps strips at a time)
+  int wps;  // wavefronts that share a strip (sweep kernel: the workgroup works on S / wps strips at a time)
+  int wpa;  // column kernel: how many of a strip's wps wavefronts take records (the others idle: a count that divides the work evenly)
   f4* ws_tiles;
   unsigned* ws_count;
 };
@@ -926,8 +927,8 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   const int ns = min(a.spw, a.n_strips - s_first);    // >= 1
   const int wps = a.wps;                              // wavefronts per strip
   const int wj = (int)((unsigned)wave / (unsigned)wps), wk = wave - wj * wps;  // this wave: strip wj of the workgroup, lane wk of its K deal
-  const bool has_strip = wj < ns;
-  const int strip = s_first + (has_strip ? wj : 0);
+  const bool has_strip = wj < ns && wk < a.wpa;
+  const int strip = s_first + (wj < ns ? wj : 0);
   // records [rec_lo, rec_hi) of every strip are this workgroup's slice of K
   const int rec_lo = a.gk > 1 ? (int)((unsigned)(gk * a.n_rec) / (unsigned)a.gk) : 0;
   const int rec_hi = a.gk > 1 ? (int)((unsigned)((gk + 1) * a.n_rec) / (unsigned)a.gk) : a.n_rec;
@@ -980,21 +981,22 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     __builtin_amdgcn_sched_barrier(0);
 
     if constexpr (QD) {
-      // Side groups dealt whole: the wave's records are its groups wk, wk + wps, ... of the phase, member by
+      // Side groups dealt whole: the wave's records are its groups wk, wk + wpa, ... of the phase, member by
       // member.  Two groups per unrolled round, so that the ring slot of a record (its number mod 4), the side
       // register of its group (the group's number mod 2) and its place in the side dword are all fixed in the
       // code.  LR = 2 records ahead as above; a group's side dword is requested with its first record.
       constexpr int UN = 2 * SG;
       const int n_grp = (n_rec + SG - 1) / SG;  // the phase starts on a group boundary; a last group may run into the padding records
-      const int cnt_g = (has_strip && wk < n_grp) ? (n_grp - wk + wps - 1) / wps : 0;
+      const int wpa = a.wpa;
+      const int cnt_g = (has_strip && wk < n_grp) ? (n_grp - wk + wpa - 1) / wpa : 0;
       const int total_e = cnt_g * SG, e_last = max(total_e - 1, 0);
       const int g_first = cnt_g > 0 ? wk : 0;
       LaneRec<FMT> ring[4];
       uint32_t side[2] = {0, 0};
-      // e-th record of this wave (clamped to its last): group g_first + (e / SG) * wps, member e % SG
+      // e-th record of this wave (clamped to its last): group g_first + (e / SG) * wpa, member e % SG
       auto request = [&](int e, LaneRec<FMT>& slot, uint32_t& side_reg, bool with_side) {
         e = min(e, e_last);
-        const int grp = rec_base / SG + g_first + (e / SG) * wps;
+        const int grp = rec_base / SG + g_first + (e / SG) * wpa;
         const uint8_t* unit = a.W + ((size_t)grp * a.n_strips + strip) * Fmt<FMT>::UNIT;
         load_lane_rec<FMT, NT, false>(slot, unit + (e % SG) * Fmt<FMT>::CB, nullptr, lane);
         if (with_side) {
@@ -1019,7 +1021,7 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
           cur.t = side[(u / SG) & 1];
           const int kk = (rel + u % SG) * REC_K;
           mac_rec<FMT, MT>(cur, x0 + kk, x1 + kk, acc, 8 * Fmt<FMT>::SIDE * (u % SG));
-          if (u % SG == SG - 1) rel += wps * SG;
+          if (u % SG == SG - 1) rel += wpa * SG;
           __builtin_amdgcn_sched_barrier(0);
         }
       };
@@ -1088,7 +1090,7 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   }
 
   // Finish the strips, one per wave: the wps tiles of a strip added in wave order.
-  if (has_strip && m_lo < mc) {
+  if (wj < ns && m_lo < mc) {  // idle wavefronts of a strip leave a tile of zeros
     f4* t = parts + (size_t)(wj * wps + wk) * part_f4 + kq * mc + m_lo;
 #pragma unroll
     for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
@@ -1333,6 +1335,7 @@ SweepPlan make_sweep_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int r
 struct ColumnPlan {
   int S, spw, grid, gn, gk, wps, rc, n_phase, x_shift, x_stride, x_region;
   bool qd;  // records dealt in whole side groups
+  int wpa;  // wavefronts of a strip that take records (= wps unless fewer divide the side groups evenly)
   size_t lds;
 };
 
@@ -1362,16 +1365,23 @@ ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int
   for (int n_phase = 1;; n_phase++) {
     int rc = (n_rec + n_phase - 1) / n_phase;
     bool qd = allow_qd && sg > 1 && gk == 1;
+    int wpa = p.wps;
     if (qd) {
+      // the most wavefronts per strip (at least 7 of 8: measured, 14 wavefronts read as fast as 16) that get the same
+      // number of groups each, within 3 %
       const int rcq = (rc + sg - 1) / sg * sg;
-      const int groups = rcq / sg, per_wave = (groups + p.wps - 1) / p.wps;
-      qd = (size_t)M * (rcq * rec_k + 8) * 2 + parts <= (size_t)kLdsMaxBytes && groups >= p.wps && per_wave * p.wps * 100 <= groups * 103;
+      const int groups = rcq / sg;
+      qd = false;
+      if ((size_t)M * (rcq * rec_k + 8) * 2 + parts <= (size_t)kLdsMaxBytes)
+        for (int w = p.wps; w * 8 >= p.wps * 7 && w >= 1 && !qd; w--)
+          if (groups >= w && (groups + w - 1) / w * w * 100 <= groups * 103) qd = true, wpa = w;
       if (qd) rc = rcq;
     }
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks
     const size_t lds = (size_t)M * x_stride * 2 + parts;
     if (lds > (size_t)kLdsMaxBytes && rc > 1) continue;  // one record per phase always fits (32 rows x 136 halfs)
     p.qd = qd;
+    p.wpa = wpa;
     p.rc = rc;
     p.n_phase = (n_rec + rc - 1) / rc;
     p.x_stride = x_stride;
@@ -1587,6 +1597,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
   a.gn = 1;
   a.gk = 1;
   a.wps = 1;
+  a.wpa = 1;
   a.ws_tiles = nullptr;
   a.ws_count = nullptr;
   a.red_slots = 0;
@@ -1612,6 +1623,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.gn = cp.gn;
     a.gk = cp.gk;
     a.wps = cp.wps;
+    a.wpa = cp.wpa;
     use_split(cp.gk);
     a.x_stride = cp.x_stride;
     a.x_region = cp.x_region;
@@ -1814,8 +1826,8 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
   const int gk = with_workspace ? choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes) : 1;
   if (f != FMT_FP16) {
     const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk);
-    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d", cp.grid,
-             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0);
+    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d", cp.grid,
+             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.wpa);
     return AMS_OK;
   }
   const SweepPlan wp = make_sweep_plan(f, M, n_strips, n_rec, rec_k, false, gk);

@@ -142,9 +142,9 @@ def random_codes(ofmt, N, K, seed):
 
 
 def cpu_baseline(shapes):
-    """The oracle as it stands (canonical unpack -> dequant -> fp64 matmul, M = 1) timed on this host: the first
-    quarter of the rows of every Linear of the 8B decode step in both formats, one pass (about 10 s of CPU work),
-    plus baseline configurations 1 and 2 in full."""
+    """The oracle as it stands (canonical unpack -> dequant -> fp64 matmul, M = 1) timed on this host: every Linear
+    of the 8B decode step in both formats, whole, one pass (about 10 s of CPU work on 16 cores, 30 s on 8), plus
+    baseline configurations 1 and 2 in full."""
     from oracle import ams_oracle as O
     from paper_2510_16045_amd import synth
 
@@ -174,7 +174,7 @@ def cpu_baseline(shapes):
     for i, (name, (N, K)) in enumerate(shapes.items()):
         X = synth.activations(1, K, 3)
         for ofmt in (O.FP533, O.FP425):
-            rows = N // 4  # bounded sample: rows are independent, every layer keeps its own K
+            rows = N  # the whole layer: about 10 s of CPU work for the set on 16 cores
             codes = random_codes(ofmt, rows, K, 77 + i)
             s = np.full(rows, 0.01, dtype=np.float16)
             nbytes, t = timed(ofmt, codes, s, X, 1)
@@ -197,7 +197,7 @@ def cpu_baseline(shapes):
         "cores": threads,
         "host_cores_available": len(os.sched_getaffinity(0)),
         "kind": "oracle",
-        "sample": "the first quarter of the rows of each of the eight Linears of the Llama-3-8B decode step (4 layers x FP5.33 + FP4.25, M=1), "
+        "sample": "the whole workload of `value`: the eight Linears of the Llama-3-8B decode step (4 layers x FP5.33 + FP4.25, M=1), "
                   "canonical unpack + dequant + fp64 matmul, one pass each, seeded random codes; `full_configs`: baseline configurations 1 and 2 whole, best of 3",
         "seconds": round(total_t, 2),
         "per_layer": per_layer,
@@ -410,7 +410,7 @@ def main():
     t_dom = time_launches(torch, lambda i: linear(dl.packed[dfmt][i % len(dl.packed[dfmt])], dl.scales[dfmt], xs[dl.name], dl.N, dfmt, ys[dl.name]), n_launch, replays=20)
     achieved = alg_bytes / t_dom / 1e3
     roofline = {
-        "bound": "hbm", "kernel": f"sweep_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
+        "bound": "hbm", "kernel": f"column_kernel<{dom['fmt']}> {dl.N}x{dl.K} M={M}",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_launch": round(t_dom, 3), "algorithmic_bytes": alg_bytes,
         "traffic": measured_traffic(ams, dl.name, dom["fmt"], M) if args.layers == "8b" else None,

@@ -84,9 +84,10 @@ int ams_code_bits(int fmt);
  * (what ams_pack writes and ams_dequant / ams_linear read): the result of the
  * "ahead-of-time weight packing" of Sec. 3.3 stage 1, arranged for 64-wide wavefronts.  The layout is opaque:
  * records of 16 rows x 96 weights (FP5.33, FP4.33, FP6) or 16 rows x 128 weights
- * (FP4.25, FP4.5, FP5, FP4), so N is padded to a multiple of 16 and K to a multiple of
- * 96 / 128; padding holds zero codes.  Without padding the size is exactly
- * N * K * bits-per-weight / 8.
+ * (FP4.25, FP4.5, FP5, FP4), stored K-major in units of 1, 2 or 4 records (formats that
+ * keep last mantissa bits beside their records: FP4.25 and FP4.33 four, FP4.5 and FP6 two),
+ * so N is padded to a multiple of 16 and K to a multiple of 96 / 128 times that unit;
+ * padding holds zero codes.  Without padding the size is exactly N * K * bits-per-weight / 8.
  */
 int ams_packed_bytes(int fmt, int64_t N, int64_t K, size_t* bytes);
 
@@ -216,8 +217,9 @@ int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, in
  */
 int ams_linear_workspace_bytes(int fmt, int M, int64_t N, int64_t K, size_t* bytes);
 /* Which kernel and launch shape ams_linear (with_workspace = 0) or ams_linear_ws (1) would use for
- * this problem (fmt = -1: the fp16 baseline), as a short text for logs and tests: "sweep ..." or
- * "stream ..." followed by key=value pairs.  Host only, launches nothing. */
+ * this problem (fmt = -1: the fp16 baseline), as a short text for logs and tests: "column ..." (the
+ * packed formats), "sweep ..." or "stream ..." (the baseline) followed by key=value pairs.  Host only,
+ * launches nothing. */
 int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, char* text, size_t text_len);
 int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
                   int64_t K, int fmt, void* workspace, size_t workspace_bytes, void* stream);
@@ -246,10 +248,12 @@ int ams_linear_static_ws(const void* W_packed, const uint16_t* scales, const uin
 
 /*
  * Measurement aid, not part of the method: a bare streaming read of the first
- * floor(bytes / 1024) KiB of `buf` (device, 16-byte aligned) in the order the Linear
- * kernel sweeps a packed matrix, nothing computed, nothing stored.  Its time is the
- * read ceiling of this GPU at that size, the second denominator (beside the 8 TB/s
- * HBM peak) for the "saturate the memory subsystem" goal of Sec. 3.3; bytes < 1024
+ * floor(bytes / 1024) KiB of `buf` (device, 16-byte aligned), front to back, 1 KiB per
+ * wavefront load, two loads in flight per wavefront, 16 wavefronts on each of 256
+ * workgroups: the window of memory that the Linear kernel's wavefronts read between them
+ * moves through a packed matrix in the same way.  Nothing is computed, nothing stored.  Its
+ * time is the read ceiling of this GPU at that size, the second denominator (beside the
+ * 8 TB/s HBM peak) for the "saturate the memory subsystem" goal of Sec. 3.3; bytes < 1024
  * gives an empty launch of the same shape (the launch floor).  `sink` is a device
  * word the kernel may write (it practically never does) or NULL.
  */

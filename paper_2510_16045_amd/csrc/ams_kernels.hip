@@ -475,9 +475,10 @@ __device__ __forceinline__ void stage_x_block(_Float16* xs, const LinearArgs& a,
 // activations of a phase are staged once per workgroup in LDS (operand order).  After
 // the last phase the wave holding a strip's first record adds the tiles of the waves
 // after it, in wave order, scales and stores.  The grid is one resident round.
-template <int FMT, int MT, int LR>
+template <int MT, int LR>
 __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int FMT = FMT_FP16;  // the baseline's kernel: row-major fp16 weights
   constexpr int REC_K = Fmt<FMT>::REC_K;
   // All kernel arguments are pulled in at once: fetched piecemeal where they are first used,
   // each batch would be one more trip to memory in front of the first weight load.
@@ -517,10 +518,6 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
   const int units_per_pass = nthr * XUnit<FMT>::XU;
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
   const int chunk_k = RC * REC_K;
-  // Scales of the first strip this wave will finish (the first one that starts inside its
-  // piece): requested before everything else and left as raw fp16 bits until the epilogue,
-  // so that nothing waits on them while the weight stream is being set up.
-  const ScaleBits scale0_bits = load_scale_bits<FMT>(a, min(strip0 + (j_first == 0 ? s_first : s_first + 1), a.n_strips - 1), lane);
   __builtin_amdgcn_sched_barrier(0);
 
   for (int rec_base = 0; rec_base < a.n_rec; rec_base += RC) {
@@ -642,7 +639,7 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
           }
         }
       }
-      store_tile_scaled<MT>(sum, s == s_begin ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip0 + s, lane), a, strip0 + s, lane);
+      store_tile_scaled<MT>(sum, f4{1.0f, 1.0f, 1.0f, 1.0f}, a, strip0 + s, lane);  // the baseline has no scales
     }
   }
 }
@@ -660,9 +657,10 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
 // order, scaled, converted, stored.  The activations are staged once per workgroup in LDS
 // in operand order; when M x K does not fit, K is walked in phases of rc records per strip
 // and the parked tiles accumulate over the phases.  The grid is one resident round.
-template <int FMT, int MT, int LR, bool NT, bool GS = false, bool GROUPS = false>
+template <int MT, int LR, bool GROUPS = false>
 __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int FMT = FMT_FP16;  // the baseline's kernel: row-major fp16 weights
   constexpr int REC_K = Fmt<FMT>::REC_K;
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
                "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wps));
@@ -708,10 +706,6 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   const int units_per_pass = nthr * XUnit<FMT>::XU;
   const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
   const int chunk_k = RC * REC_K;
-  // Scales of the first strip this wave finishes: requested first, kept as raw bits until the epilogue.
-  // (With one scale per run of input channels, GS, the scales travel with the records instead.)
-  ScaleBits scale0_bits = {{0x3C00, 0x3C00, 0x3C00, 0x3C00}};
-  if constexpr (!GS) scale0_bits = load_scale_bits<FMT>(a, min(g + min(wave, ns - 1) * G, a.n_strips - 1), lane);
   __builtin_amdgcn_sched_barrier(0);
 
   // K is walked in phases of RC records per strip (one phase when all activations fit in LDS).
@@ -750,14 +744,11 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     constexpr int RS = LR + 1;
     struct Slot {
       LaneRec<FMT> r;
-      us4 gs;  // GS: the scales of this lane's four output channels for the record's run
     };
     Slot ring[RS];
     auto request = [&](Slot& slot) {
       const int strip = strip0 + pj * strip_step;
-      load_rec<FMT, NT>(slot.r, a, strip, rec_base + pr, lane);
-      if constexpr (GS)  // 8 bytes, the same for the 16 lanes of a K-quarter; cached: a run spans many records
-        slot.gs = *(const us4*)(a.scales + ((size_t)strip * a.n_sg + ((rec_base + pr) >> a.sg_shift)) * 16 + 4 * kq);
+      load_rec<FMT, false>(slot.r, a, strip, rec_base + pr, lane);
       if (pf + wps < total) {
         pf += wps, pr += wps;
         while (pr >= n_rec) pr -= n_rec, pj++;
@@ -800,19 +791,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     auto step = [&](Slot& slot, Slot& free_slot) {
       request(free_slot);
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (GS) {  // the record's own tile, times its run's scales (Eq. 2), then into the sum
-        f4 t[MT];
-#pragma unroll
-        for (int i = 0; i < MT; i++) t[i] = f4{0, 0, 0, 0};
-        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, t);
-        f4 sc;
-#pragma unroll
-        for (int r = 0; r < 4; r++) sc[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)slot.gs[r]);
-#pragma unroll
-        for (int i = 0; i < MT; i++) acc[i] += t[i] * sc;
-      } else {
-        mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc);
-      }
+      mac_rec<FMT, MT>(slot.r, x0 + cr * REC_K, x1 + cr * REC_K, acc);
       pending = true;
       cr += wps;
       if (cr >= n_rec) {
@@ -887,12 +866,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
       }
       if (lane == 0) __hip_atomic_store(a.ws_count + strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    f4 sc;
-    if constexpr (GS)
-      sc = f4{kTwo14, kTwo14, kTwo14, kTwo14};
-    else
-      sc = j == wave ? scales_from_bits(scale0_bits, FMT == FMT_FP16 ? 1.0f : kTwo14) : load_scales<FMT>(a, strip, lane);
-    store_tile_scaled<MT>(sum, sc, a, strip, lane);
+    store_tile_scaled<MT>(sum, f4{1.0f, 1.0f, 1.0f, 1.0f}, a, strip, lane);  // the baseline has no scales
   }
 }
 
@@ -1527,17 +1501,14 @@ enum KernelKind { kSweep, kStream };
 // The fp16 baseline's kernels by ring depth and wave grouping.
 template <int MT>
 int launch_fp16(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
-  constexpr int FMT = FMT_FP16;
   const bool groups = a.wps != S;  // wave groups per strip: their own instantiation, the common case stays lean
   if (kind == kSweep) {
-    if (lr == 1)
-      return groups ? launch(sweep_kernel<FMT, MT, 1, false, false, true>, a, grid, S, lds, st)
-                    : launch(sweep_kernel<FMT, MT, 1, false, false, false>, a, grid, S, lds, st);
-    if (lr == 2 && !groups) return launch(sweep_kernel<FMT, MT, 2, false, false, false>, a, grid, S, lds, st);
+    if (lr == 1) return groups ? launch(sweep_kernel<MT, 1, true>, a, grid, S, lds, st) : launch(sweep_kernel<MT, 1, false>, a, grid, S, lds, st);
+    if (lr == 2 && !groups) return launch(sweep_kernel<MT, 2, false>, a, grid, S, lds, st);
   } else {
     switch (lr) {
-      case 4: return launch(stream_kernel<FMT, MT, 4>, a, grid, S, lds, st);
-      case 2: return launch(stream_kernel<FMT, MT, 2>, a, grid, S, lds, st);
+      case 4: return launch(stream_kernel<MT, 4>, a, grid, S, lds, st);
+      case 2: return launch(stream_kernel<MT, 2>, a, grid, S, lds, st);
     }
   }
   return AMS_ERR_LAUNCH;

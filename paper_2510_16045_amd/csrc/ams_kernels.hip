@@ -426,10 +426,16 @@ __device__ __forceinline__ void store_tile_scaled(const f4 t[MT], const f4 sc, c
   for (int mt = 0; mt < MT; mt++) {
     const int m = m_lo + 16 * mt;
     if (m < a.M) {
+      const int n0 = strip * 16 + 4 * kq;
+      us4 h;
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int n = strip * 16 + 4 * kq + r;
-        if (n < a.N) a.Y[(size_t)m * a.N + n] = __builtin_bit_cast(uint16_t, (_Float16)(t[mt][r] * sc[r]));
+      for (int r = 0; r < 4; r++) h[r] = __builtin_bit_cast(uint16_t, (_Float16)(t[mt][r] * sc[r]));
+      if (n0 + 3 < a.N && (a.N & 3) == 0) {  // the lane's four output channels are eight aligned bytes of Y's row m
+        *(us4*)(a.Y + (size_t)m * a.N + n0) = h;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+          if (n0 + r < a.N) a.Y[(size_t)m * a.N + n0 + r] = h[r];
       }
     }
   }

@@ -327,21 +327,23 @@ template <int FMT>
 struct XUnit {
   static constexpr int UNIT = Fmt<FMT>::PB;               // halfs permuted together
   static constexpr int CH = UNIT / 8;                     // 16-byte chunks per unit
-  static constexpr int XU = 2;                            // units a lane moves per pass
+  static constexpr int XU = 2;                            // units a lane moves in the first pass (in flight with the weights)
+  static constexpr int XB = CH == 1 ? 8 : CH == 2 ? 4 : 2;  // units a lane moves in each further pass (all requested, then stored)
 };
 
-template <int FMT>
+template <int FMT, int NU = XUnit<FMT>::XU>
 struct XRegs {
-  u4 c[XUnit<FMT>::XU][XUnit<FMT>::CH];
+  u4 c[NU][XUnit<FMT>::CH];
 };
 
-template <int FMT>
-__device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int k0, int nk, int pass, int idx, int nthr) {
-  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
+// Units u0 + i * nthr + idx, i < NU.
+template <int FMT, int NU>
+__device__ __forceinline__ void x_load(XRegs<FMT, NU>& xr, const LinearArgs& a, int k0, int nk, int u0, int idx, int nthr) {
+  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH;
   const int upr = nk / UNIT;
 #pragma unroll
-  for (int i = 0; i < XU; i++) {
-    const int u = (pass * XU + i) * nthr + idx;
+  for (int i = 0; i < NU; i++) {
+    const int u = u0 + i * nthr + idx;
     const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
     const int k = k0 + UNIT * j;
     const bool row_ok = m < a.M && j < upr;
@@ -354,14 +356,14 @@ __device__ __forceinline__ void x_load(XRegs<FMT>& xr, const LinearArgs& a, int 
   }
 }
 
-template <int FMT>
-__device__ __forceinline__ void x_store(const XRegs<FMT>& xr, _Float16* xs, const LinearArgs& a, int k0, int nk, int pass,
+template <int FMT, int NU>
+__device__ __forceinline__ void x_store(const XRegs<FMT, NU>& xr, _Float16* xs, const LinearArgs& a, int k0, int nk, int u0,
                                         int idx, int nthr) {
-  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH, XU = XUnit<FMT>::XU;
+  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH;
   const int upr = nk / UNIT;
 #pragma unroll
-  for (int i = 0; i < XU; i++) {
-    const int u = (pass * XU + i) * nthr + idx;
+  for (int i = 0; i < NU; i++) {
+    const int u = u0 + i * nthr + idx;
     const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
     const int k = k0 + UNIT * j;
     uint32_t in[4 * CH], out[4 * CH];
@@ -536,14 +538,15 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
     const int k0 = rec_base * REC_K;
     XRegs<FMT> xr;
     if (vec_x) {
-      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
-        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
-        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
+      for (int u0 = units_per_pass; u0 < total_units; u0 += nthr * XUnit<FMT>::XB) {
+        XRegs<FMT, XUnit<FMT>::XB> xb;
+        x_load(xb, a, k0, chunk_k, u0, tid, nthr);
+        x_store(xb, xs, a, k0, chunk_k, u0, tid, nthr);
       }
     } else {
       stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
     }
-    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    if (wave_has_x) x_load(xr, a, k0, chunk_k, 0, tid, nthr);
     __builtin_amdgcn_sched_barrier(0);
 
     // the head of the weight stream: LR records in flight per wave.  The prefetch cursor
@@ -566,7 +569,7 @@ __global__ void __launch_bounds__(1024) stream_kernel(LinearArgs a) {
       // set-up that nothing above needs, done while the first loads are in flight: this wave's tile slots cleared
       for (int t = 0; t < a.red_slots * MT; t++) my_red[t * 64] = f4{0, 0, 0, 0};
     }
-    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+    if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
     __syncthreads();
 
     f4 acc[MT];
@@ -727,14 +730,15 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     // head of the weight stream, so both are in flight together.
     XRegs<FMT> xr;
     if (vec_x) {
-      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
-        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
-        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
+      for (int u0 = units_per_pass; u0 < total_units; u0 += nthr * XUnit<FMT>::XB) {
+        XRegs<FMT, XUnit<FMT>::XB> xb;
+        x_load(xb, a, k0, chunk_k, u0, tid, nthr);
+        x_store(xb, xs, a, k0, chunk_k, u0, tid, nthr);
       }
     } else {
       stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
     }
-    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    if (wave_has_x) x_load(xr, a, k0, chunk_k, 0, tid, nthr);
     __builtin_amdgcn_sched_barrier(0);
 
     // Head of the weight stream.  The prefetch cursor (position in the list, local strip,
@@ -770,7 +774,7 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
     // strip has fewer records than the workgroup has waves)
     if (rec_base == rec_lo)
       for (int i = tid; i < ns * wps * part_f4; i += nthr) parts[i] = f4{0, 0, 0, 0};
-    if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+    if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
     __syncthreads();
 
     f4 acc[MT];
@@ -950,14 +954,15 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     // head of the weight stream, so both are in flight together.
     XRegs<FMT> xr;
     if (vec_x) {
-      for (int pass = 1; pass * units_per_pass < total_units; pass++) {
-        x_load<FMT>(xr, a, k0, chunk_k, pass, tid, nthr);
-        x_store<FMT>(xr, xs, a, k0, chunk_k, pass, tid, nthr);
+      for (int u0 = units_per_pass; u0 < total_units; u0 += nthr * XUnit<FMT>::XB) {
+        XRegs<FMT, XUnit<FMT>::XB> xb;
+        x_load(xb, a, k0, chunk_k, u0, tid, nthr);
+        x_store(xb, xs, a, k0, chunk_k, u0, tid, nthr);
       }
     } else {
       stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
     }
-    if (wave_has_x) x_load<FMT>(xr, a, k0, chunk_k, 0, tid, nthr);
+    if (wave_has_x) x_load(xr, a, k0, chunk_k, 0, tid, nthr);
     __builtin_amdgcn_sched_barrier(0);
 
     if constexpr (QD) {
@@ -988,7 +993,7 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       request(1, ring[1], side[(1 / SG) & 1], 1 % SG == 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+      if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
       __syncthreads();
 
       int rel = g_first * SG;  // first record of the group being multiplied, relative to the phase
@@ -1031,7 +1036,7 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
         request(ring[q]);
         __builtin_amdgcn_sched_barrier(0);  // issue in ring order: the oldest load is the first one needed
       }
-      if (wave_has_x) x_store<FMT>(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+      if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
       __syncthreads();
 
       // One record: request the one LR ahead, restore, multiply, move on by wps records.

@@ -364,3 +364,28 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_device_entry_points_refuse_a_machine_without_the_gpu():
+    # Argument checks come first, then the device check, then the launch: with valid-looking arguments and no
+    # gfx950 current every device entry point returns AMS_ERR_DEVICE and never touches the pointers.
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: the device entry points would run")
+    lib = ams.load_library()
+    AMS_ERR_DEVICE = -7
+    assert lib.ams_init() == AMS_ERR_DEVICE
+    assert b"gfx950" in lib.ams_strerror(AMS_ERR_DEVICE)
+    p = ctypes.c_void_p(1 << 20)  # aligned, never dereferenced
+    M, N, K = 1, 256, 768
+    assert lib.ams_linear(p, p, p, p, M, N, K, ams.FP425, None) == AMS_ERR_DEVICE
+    assert lib.ams_linear_ws(p, p, p, p, M, N, K, ams.FP533, p, 1 << 20, None) == AMS_ERR_DEVICE
+    assert lib.ams_linear_static_ws(p, p, p, p, M, N, K, ams.FP533, None) == AMS_ERR_DEVICE
+    assert lib.ams_fp16_linear(p, p, p, M, N, K, None) == AMS_ERR_DEVICE
+    assert lib.ams_dequant(ams.FP425, p, p, p, N, K, 1, None) == AMS_ERR_DEVICE
+    assert lib.ams_read_probe(p, 4096, None, None) == AMS_ERR_DEVICE
+    # argument errors still win over the device error
+    assert lib.ams_linear(None, p, p, p, M, N, K, ams.FP425, None) == -3  # AMS_ERR_NULL
+    assert lib.ams_linear(p, p, p, p, 33, N, K, ams.FP425, None) == -2  # AMS_ERR_SHAPE
+    with pytest.raises(ams.AmsError):
+        ams.ams_init()

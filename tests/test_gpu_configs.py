@@ -1,7 +1,8 @@
 """GPU parity on the benchmark configurations at their full sizes, in the launch configuration
 bench.py times: the Llama-70B-shaped layers on heavy-tailed weights with outliers (both paper
-formats, M in {1, 4, 8}), the Llama-8B qkv and down projections, and the Qwen2.5-7B down
-projection of Table 3.  The oracle quantizes a sample of rows (rows are independent: first and
+formats, M in {1, 4, 8}), the Llama-8B qkv and down projections, the batch sweep on the Llama-8B
+gate/up and down projections (M = 1 .. 32, with and without a split of K), and the Qwen down
+projections of Table 3.  The oracle quantizes a sample of rows (rows are independent: first and
 last strip, a workgroup boundary, a stride through the matrix) and checks those outputs; the
 restored weights of the sampled strips must match bit for bit."""
 
@@ -48,7 +49,7 @@ def sampled_strips(N: int, stride: int) -> np.ndarray:
     return np.unique(s[s < n_strips])
 
 
-def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False):
+def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False, with_static=False):
     strips = sampled_strips(N, stride)
     rows = np.concatenate([np.arange(16 * t, min(N, 16 * t + 16)) for t in strips])
     ws = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda") if with_workspace else None
@@ -75,6 +76,9 @@ def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False):
             if ws is not None:
                 y = host16(ams.ams_linear_ws(wp, sc, x, N, fmt, ws))
                 check_linear(y[:, rows], ref, f"{ofmt.name} N={N} K={K} M={M} (workspace)")
+            if with_static:
+                y = host16(ams.ams_linear_static_ws(wp, sc, x, N, fmt))
+                check_linear(y[:, rows], ref, f"{ofmt.name} N={N} K={K} M={M} (static scratch)")
         del wp, sc
 
 
@@ -93,6 +97,15 @@ def test_llama8b_layers_small_batches(layer, stride):
     N, K = synth.LLAMA8B_LAYERS[layer]
     W = synth.gaussian_weights(N, K, 710 + len(layer))
     check_shape_against_oracle(N, K, W, (1, 2), stride)
+
+
+@pytest.mark.parametrize("layer,stride", [("gate_up", 173), ("down", 41)])
+def test_llama8b_batch_sweep(layer, stride):
+    # the batch sweep the benchmark times: every batch size, through the plain entry point, the caller's
+    # workspace and the library's static scratch
+    N, K = synth.LLAMA8B_LAYERS[layer]
+    W = synth.gaussian_weights(N, K, 730 + len(layer))
+    check_shape_against_oracle(N, K, W, (1, 2, 4, 8, 16, 32), stride, with_workspace=True, with_static=True)
 
 
 @pytest.mark.parametrize("model,Ms", [("qwen2.5-7b", (1, 2, 16)), ("qwen3-4b", (1, 32))])

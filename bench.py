@@ -53,6 +53,7 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep M=1..32 (gate/up and down of the 8B set)")
     ap.add_argument("--sweep-all-layers", action="store_true", help="sweep every layer of the set, not only gate/up and down")
     ap.add_argument("--no-70b", action="store_true", help="skip the Llama-70B-shaped layers at M=1,4,8")
+    ap.add_argument("--no-lm-head", action="store_true", help="skip the Llama-3-8B vocabulary projection (128256 x 4096) at M=1,8")
     ap.add_argument("--out", default=None, help="also write the sweep table to this file")
     ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all seven formats (the step keeps the paper's two)")
     ap.add_argument("--group-scales", action="store_true", help="also time ams_linear_grouped (one scale per record-sized run of K) per layer")
@@ -428,19 +429,14 @@ def main():
             with open(args.out, "w") as f:
                 json.dump({"layers": args.layers, "sweep": sweep}, f, indent=1)
 
-    # ---- the Llama-70B-shaped layers (heavy-tailed weights with outliers) at M = 1, 4, 8
-    llama70b = None
-    if not args.no_70b and args.layers == "8b":
-        del layers, dl, xs, ys
-        l = None
-        gc.collect()
-        torch.cuda.empty_cache()
+    # ---- larger layers, each set built, timed and freed by itself
+    def measure_set(shape_set, maker, seed, batches, label):
         t_setup = time.perf_counter()
-        big, _ = build_layers(synth.LLAMA70B_LAYERS, synth.heavy_tail_weights, 200, fmts, args.copies_mb, ams, torch)
-        print(f"# 70B setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr)
-        llama70b = []
+        big, _ = build_layers(shape_set, maker, seed, fmts, args.copies_mb, ams, torch)
+        print(f"# {label} setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr)
+        rows = []
         for l in big:
-            for Mb in (1, 4, 8):
+            for Mb in batches:
                 x = to_dev(synth.activations(Mb, l.K, 11), torch)
                 y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
                 nl = 4 * max(len(l.w16), 2)
@@ -448,7 +444,7 @@ def main():
                 tlib = time_launches(torch, lambda i: torch.matmul(x, l.w16[i % len(l.w16)].t(), out=y), nl)
                 for fmt in fmts:
                     pk, sc = l.packed[fmt], l.scales[fmt]
-                    nl = 4 * len(pk)
+                    nl = 4 * max(len(pk), 2)
                     t = time_launches(torch, lambda i: ams.ams_linear(pk[i % len(pk)], sc, x, l.N, fmt, out=y), nl)
                     try:
                         tws = time_launches(torch, lambda i: ams.ams_linear_static_ws(pk[i % len(pk)], sc, x, l.N, fmt, out=y), nl)
@@ -456,15 +452,29 @@ def main():
                         tws = None
                     t_read = time_launches(torch, lambda i: ams.ams_read_probe(pk[i % len(pk)]), nl) if Mb == 1 else None
                     gbps = l.canon[fmt] / t / 1e3
-                    llama70b.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
-                                     "us_static_ws": None if tws is None else round(tws, 3),
-                                     "bare_read_us": None if t_read is None else round(t_read, 3),
-                                     "GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
-                                     "fp16_us": round(t16, 3), "library_gemm_fp16_us": round(tlib, 3),
-                                     "speedup_vs_fp16": round(t16 / t, 3), "speedup_vs_best_fp16": round(min(t16, tlib) / t, 3)})
+                    rows.append({"layer": l.name, "N": l.N, "K": l.K, "M": Mb, "fmt": FMT_NAMES[fmt], "us": round(t, 3),
+                                 "us_static_ws": None if tws is None else round(tws, 3),
+                                 "bare_read_us": None if t_read is None else round(t_read, 3),
+                                 "GBps": round(gbps, 1), "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                                 "fp16_us": round(t16, 3), "library_gemm_fp16_us": round(tlib, 3),
+                                 "speedup_vs_fp16": round(t16 / t, 3), "speedup_vs_best_fp16": round(min(t16, tlib) / t, 3)})
         del big
         gc.collect()
         torch.cuda.empty_cache()
+        return rows
+
+    llama70b = lm_head = None
+    if args.layers == "8b" and not (args.no_70b and args.no_lm_head):
+        del layers, dl, xs, ys
+        l = None
+        gc.collect()
+        torch.cuda.empty_cache()
+        # the Llama-70B-shaped layers (heavy-tailed weights with outliers) at M = 1, 4, 8
+        if not args.no_70b:
+            llama70b = measure_set(synth.LLAMA70B_LAYERS, synth.heavy_tail_weights, 200, (1, 4, 8), "70B")
+        # the output projection onto the vocabulary, the largest Linear of a Llama-3-8B decode step
+        if not args.no_lm_head:
+            lm_head = measure_set({"lm_head": synth.LLAMA8B_LM_HEAD}, synth.gaussian_weights, 300, (1, 8), "lm_head")
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(synth.LLAMA8B_LAYERS)
 
@@ -489,6 +499,9 @@ def main():
         "batch_sweep": sweep,
         # baseline configuration 5: Student-t(4) x 0.02 weights with 0.1 % outliers x 20
         "llama70b": llama70b,
+        # Llama-3-8B's vocabulary projection (128256 x 4096): a Linear large enough that the launch floor and the
+        # epilogue stop mattering
+        "lm_head": lm_head,
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",
     }
     print(json.dumps(line))

@@ -24,6 +24,7 @@ LLAMA8B_LAYERS = {
     "gate_up": (28672, 4096),
     "down": (4096, 14336),
 }
+LLAMA8B_LM_HEAD = (128256, 4096)  # the vocabulary projection of Llama-3-8B
 LLAMA70B_LAYERS = {
     "o": (8192, 8192),
     "gate_up": (57344, 8192),

@@ -41,16 +41,16 @@ def check_linear(y_gpu: np.ndarray, ref: np.ndarray, what=""):
     assert mx <= MAX_ABS_TOL, f"{what}: max abs / rms {mx}"
 
 
-def sampled_strips(N: int, stride: int) -> np.ndarray:
+def sampled_strips(N: int, stride: int, extra=()) -> np.ndarray:
     """Strips of 16 rows: the first, the last, the ones around workgroup 255 / 256 (the grid has 256
     workgroups and strips are dealt round robin), and every stride-th."""
     n_strips = -(-N // 16)
-    s = np.r_[0, n_strips - 1, 254:258, np.arange(3, n_strips, stride)]
+    s = np.r_[0, n_strips - 1, 254:258, np.arange(3, n_strips, stride), np.asarray(extra, dtype=np.int64)]
     return np.unique(s[s < n_strips])
 
 
-def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False, with_static=False):
-    strips = sampled_strips(N, stride)
+def check_shape_against_oracle(N, K, W, Ms, stride, with_workspace=False, with_static=False, extra_strips=()):
+    strips = sampled_strips(N, stride, extra_strips)
     rows = np.concatenate([np.arange(16 * t, min(N, 16 * t + 16)) for t in strips])
     ws = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda") if with_workspace else None
     for fmt, ofmt in PAPER_PAIRS:
@@ -106,6 +106,14 @@ def test_llama8b_batch_sweep(layer, stride):
     N, K = synth.LLAMA8B_LAYERS[layer]
     W = synth.gaussian_weights(N, K, 730 + len(layer))
     check_shape_against_oracle(N, K, W, (1, 2, 4, 8, 16, 32), stride, with_workspace=True, with_static=True)
+
+
+def test_llama8b_vocabulary_projection():
+    # 128256 x 4096: 8016 strips, 16 per workgroup, 501 workgroups on 256 compute units (two rounds); sampled
+    # strips include both sides of the boundary between the rounds and of a workgroup
+    N, K = synth.LLAMA8B_LM_HEAD
+    W = synth.gaussian_weights(N, K, 740)
+    check_shape_against_oracle(N, K, W, (1, 8), 499, with_static=True, extra_strips=(15, 16, 4095, 4096, 8000, 8015))
 
 
 @pytest.mark.parametrize("model,Ms", [("qwen2.5-7b", (1, 2, 16)), ("qwen3-4b", (1, 32))])

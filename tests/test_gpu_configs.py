@@ -122,3 +122,11 @@ def test_qwen_down_projections(model, Ms):
     N, K = synth.QWEN_DOWN_LAYERS[model]
     W = synth.gaussian_weights(N, K, 720 + len(model))
     check_shape_against_oracle(N, K, W, Ms, 23, with_workspace=True)
+
+
+@pytest.mark.parametrize("N,K,Ms", [(1_000_003, 100, (1, 5)), (20, 1_000_000, (1, 5, 32))])
+def test_extreme_aspect_ratios(N, K, Ms):
+    # a million rows of two records each (62501 strips: thousands of workgroups in many rounds), and two strips
+    # of ten thousand records (K walked in phases from M = 5 on, split over workgroups when a workspace is given)
+    W = synth.gaussian_weights(N, K, 750 + (N % 7))
+    check_shape_against_oracle(N, K, W, Ms, 4999, with_workspace=N < 100, with_static=N < 100)

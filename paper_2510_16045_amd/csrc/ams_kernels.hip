@@ -880,6 +880,94 @@ __global__ void __launch_bounds__(1024) sweep_kernel(LinearArgs a) {
   }
 }
 
+// The fp16 baseline at small batches (Sec. 4.2's W16A16 GEMV): every wavefront owns whole rows of the
+// row-major matrix, dealt round robin over all wavefronts of the grid, and reads a row as consecutive
+// 1 KiB segments (one 16-byte load per lane, LR of them in flight), multiplies on the VALU (packed dot
+// products into fp32, the lane's eight channels against the same eight of each activation row in LDS)
+// and adds the 64 lanes of a row up when the row ends.  a.x_stride = halfs between activation rows in
+// LDS (K rounded up to whole segments; the tail is zero).  K is a multiple of 8.
+template <int MB, bool NT>
+__global__ void __launch_bounds__(1024) gemv_fp16_kernel(LinearArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  constexpr int LR = 2, RS = LR + 1, SEG = 512;  // halfs of a row one wavefront load covers
+  _Float16* xs = (_Float16*)smem;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_seg = (a.K + SEG - 1) / SEG;
+  const int kpad = a.x_stride;
+  for (int u = tid; u < MB * (kpad / 8); u += 1024) {
+    const int m = u / (kpad / 8), k = 8 * (u - m * (kpad / 8));
+    u4 v = u4{0, 0, 0, 0};
+    if (k < a.K) v = *(const u4*)(a.X + (size_t)m * a.K + k);
+    *(u4*)(xs + (size_t)m * kpad + k) = v;
+  }
+  __syncthreads();
+
+  const int n_waves = gridDim.x * 16;
+  const int first = __builtin_amdgcn_readfirstlane(blockIdx.x * 16 + wave);  // this wave's first row
+  const int n_rows = first < a.N ? (a.N - first + n_waves - 1) / n_waves : 0;
+  const int total = n_rows * n_seg;  // segments this wave reads, row after row
+  if (total == 0) return;
+  const _Float16* W = (const _Float16*)a.W;
+  u4 ring[RS];
+  int rq = 0;  // next segment to request (clamped to the last: requests past the end are ignored)
+  auto request = [&](u4& slot) {
+    const int c = min(rq, total - 1);
+    const int ri = c / n_seg, seg = c - ri * n_seg;
+    const int k = seg * SEG + 8 * lane;
+    const bool ok = k < a.K;
+    const u4* p = (const u4*)(W + (size_t)(first + ri * n_waves) * a.K + (ok ? k : 0));
+    const u4 v = NT ? __builtin_nontemporal_load(p) : *p;
+    const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;  // lanes beyond K re-read the row's start and drop it
+    slot = u4{v[0] & keep, v[1] & keep, v[2] & keep, v[3] & keep};
+    rq++;
+  };
+#pragma unroll
+  for (int q = 0; q < LR; q++) {
+    request(ring[q]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float acc[MB];
+#pragma unroll
+  for (int m = 0; m < MB; m++) acc[m] = 0.0f;
+  int row = first, seg = 0;
+  auto step = [&](u4& slot, u4& free_slot) {
+    request(free_slot);
+    __builtin_amdgcn_sched_barrier(0);
+    const h8 w = __builtin_bit_cast(h8, slot);
+    const _Float16* x = xs + seg * SEG + 8 * lane;
+#pragma unroll
+    for (int m = 0; m < MB; m++) {
+      const h8 xv = *(const h8*)(x + (size_t)m * kpad);
+#pragma unroll
+      for (int q = 0; q < 4; q++) acc[m] = __builtin_amdgcn_fdot2(h2{w[2 * q], w[2 * q + 1]}, h2{xv[2 * q], xv[2 * q + 1]}, acc[m], false);
+    }
+    if (++seg == n_seg) {  // the row is complete: add its 64 lanes up and store
+#pragma unroll
+      for (int m = 0; m < MB; m++) {
+        float v = acc[m];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+        if (lane == 0) a.Y[(size_t)m * a.N + row] = __builtin_bit_cast(uint16_t, (_Float16)v);
+        acc[m] = 0.0f;
+      }
+      seg = 0;
+      row += n_waves;
+    }
+  };
+  int i = 0;
+  for (; i + RS <= total; i += RS) {
+#pragma unroll
+    for (int q = 0; q < RS; q++) {
+      step(ring[q], ring[(q + LR) % RS]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < RS - 1; q++)
+    if (i + q < total) step(ring[q], ring[(q + LR) % RS]);
+}
+
 // The Linear on packed weights.  A workgroup owns up to 16 neighbouring strips (spw of them,
 // one resident round of workgroups; more strips than 16 x 256 just means more workgroups) and
 // has S / spw wavefronts on each: a wavefront stays with its strip and takes every wps-th
@@ -1389,6 +1477,20 @@ size_t split_workspace_bytes(int M, int64_t n_strips, int gk) {
   return gk <= 1 ? 0 : kSplitCounterBytes + (size_t)gk * n_strips * (M > 16 ? 2 : 1) * 1024;
 }
 
+// The baseline's GEMV kernel takes batches up to 4 whose activations fit in LDS beside nothing else.
+struct GemvPlan {
+  bool ok;
+  int kpad;    // K rounded up to whole 512-channel segments
+  size_t lds;  // M rows of kpad halfs
+};
+GemvPlan make_gemv_plan(int M, int64_t K, int gk) {
+  GemvPlan p;
+  p.kpad = (int)((K + 511) / 512 * 512);
+  p.lds = (size_t)M * p.kpad * 2;
+  p.ok = M <= 4 && gk == 1 && K % 8 == 0 && p.lds <= (size_t)kLdsMaxBytes;
+  return p;
+}
+
 constexpr int kMaxSplit = 8;  // most slices of K choose_split ever takes
 // passed as the workspace by the entry point that uses the library's static scratch instead
 void* const kStaticScratch = (void*)(uintptr_t)1;
@@ -1525,6 +1627,17 @@ int launch_fp16(KernelKind kind, int lr, const LinearArgs& a, unsigned grid, int
   return AMS_ERR_LAUNCH;
 }
 
+// The baseline's GEMV kernel by batch size.
+int launch_gemv(int M, bool nt, const LinearArgs& a, unsigned grid, size_t lds, hipStream_t st) {
+  switch (M) {
+    case 1: return nt ? launch(gemv_fp16_kernel<1, true>, a, grid, 16, lds, st) : launch(gemv_fp16_kernel<1, false>, a, grid, 16, lds, st);
+    case 2: return nt ? launch(gemv_fp16_kernel<2, true>, a, grid, 16, lds, st) : launch(gemv_fp16_kernel<2, false>, a, grid, 16, lds, st);
+    case 3: return nt ? launch(gemv_fp16_kernel<3, true>, a, grid, 16, lds, st) : launch(gemv_fp16_kernel<3, false>, a, grid, 16, lds, st);
+    case 4: return nt ? launch(gemv_fp16_kernel<4, true>, a, grid, 16, lds, st) : launch(gemv_fp16_kernel<4, false>, a, grid, 16, lds, st);
+  }
+  return AMS_ERR_LAUNCH;
+}
+
 // The packed formats' kernel: nt = non-temporal weight loads, gs = one scale per run of input channels.
 template <int FMT, int MT>
 int launch_column(bool nt, bool gs, bool qd, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
@@ -1619,6 +1732,11 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st)
                    : launch_column<FMT, 2>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st);
   } else {
+    if (const GemvPlan gp = make_gemv_plan(M, K, gk); gp.ok) {
+      a.x_stride = gp.kpad;
+      const bool nt = N * K * 2 >= (2ll << 20);
+      return launch_gemv(M, nt, a, kNumCU, gp.lds, st);
+    }
     const SweepPlan wp = make_sweep_plan(FMT, M, n_strips, n_rec, REC_K, false, gk);
     if (wp.ok) {
       a.gn = wp.gn;
@@ -1662,6 +1780,8 @@ int prepare_format() {
           ok &= launch_column<FMT, 2>(nt, gs, qd, a, 0, 16, 0, nullptr) == AMS_OK;
         }
   } else {
+    for (int m = 1; m <= 4; m++)
+      for (int nt = 0; nt < 2; nt++) ok &= launch_gemv(m, nt != 0, a, 0, 0, nullptr) == AMS_OK;
     for (int groups = 0; groups < 2; groups++) {
       a.wps = groups ? 8 : 16;
       ok &= launch_fp16<1>(kSweep, 1, a, 0, 16, 0, nullptr) == AMS_OK;
@@ -1810,6 +1930,11 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
     const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk);
     snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d", cp.grid,
              cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.wpa);
+    return AMS_OK;
+  }
+  if (const GemvPlan gp = make_gemv_plan(M, K, gk); gp.ok) {
+    snprintf(text, text_len, "gemv grid=%d rows_per_wave=%d k_slices=1 waves=16 phases=1 lds=%zu", kNumCU,
+             (int)((N + kNumCU * 16 - 1) / (kNumCU * 16)), gp.lds);
     return AMS_OK;
   }
   const SweepPlan wp = make_sweep_plan(f, M, n_strips, n_rec, rec_k, false, gk);

@@ -393,6 +393,37 @@ def test_linear_with_workspace_matches_oracle(fmt, ofmt):
     assert not ws[: 4 * 16384].any()
 
 
+@pytest.mark.parametrize(
+    "N,K",
+    [(1, 8), (37, 1000), (5000, 520), (4097, 512), (9000, 24), (256, 40960), (28672, 4096)],
+)
+def test_fp16_baseline_small_batches_rows_dealt_to_wavefronts(N, K):
+    # batches up to 4 take the GEMV form: whole rows per wavefront (more rows than the grid has wavefronts, fewer,
+    # one), 512-channel segments with a ragged last one, rows as long as LDS holds activations for
+    W = synth.gaussian_weights(N, K, 75)
+    w = dev(W)
+    rows = np.unique(np.r_[0 : min(N, 32), max(N - 32, 0) : N, np.arange(0, N, 211), 4090 : min(N, 4100)])
+    for M in (1, 2, 3, 4):
+        if "gemv" not in ams.ams_linear_plan(-1, M, N, K):
+            assert 2 * M * K > 150 * 1024  # only activations that do not fit in LDS go elsewhere
+            continue
+        X = synth.activations(M, K, 75 + M)
+        y = host16(ams.ams_fp16_linear(w, dev(X)))
+        assert np.all(np.isfinite(y.astype(np.float32)))
+        check_linear(y[:, rows], O.fp16_linear(W[rows], X), f"fp16 N={N} K={K} M={M}")
+
+
+def test_fp16_baseline_keeps_subnormal_weights():
+    # weights below the smallest normal binary16 must count (the restored packed weights live there too)
+    rng = np.random.default_rng(5)
+    N, K = 300, 1024
+    W = (rng.integers(1, 1024, size=(N, K)).astype(np.uint16) | (rng.integers(0, 2, size=(N, K)).astype(np.uint16) << 15)).view(np.float16)
+    X = synth.activations(2, K, 6)
+    y = host16(ams.ams_fp16_linear(dev(W), dev(X)))
+    check_linear(y, O.fp16_linear(W, X), "subnormal weights")
+    assert np.count_nonzero(y) > y.size // 2
+
+
 def test_fp16_baseline_with_workspace_matches_oracle():
     ws = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
     for N, K, M in [(6144, 4096, 4), (5000, 4104, 8), (3000, 6008, 32)]:

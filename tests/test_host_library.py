@@ -265,7 +265,9 @@ def test_launch_plans_cover_the_kernels_and_the_split():
     assert int(plan(ams.FP425, 8, 4096, 14336)["phases"]) > 1
     assert plan(ams.FP425, 8, 4096, 14336, with_workspace=True)["k_slices"] == "4"
     assert plan(ams.FP425, 1, 4096, 14336, with_workspace=True)["k_slices"] == "1"
-    assert kind(-1, 1, 4096, 4096) == "sweep"
+    assert kind(-1, 1, 4096, 4096) == "gemv" and kind(-1, 4, 28672, 4096) == "gemv"  # small batches: rows dealt to wavefronts
+    assert kind(-1, 4, 8192, 28672) == "sweep"  # four rows of 28672 activations do not fit in LDS
+    assert kind(-1, 8, 4096, 4096) == "sweep"
     assert kind(-1, 32, 57344, 8192) == "stream"  # the baseline with many parked tiles and more than two phases
     for fmt, _ in PAIRS:
         for M in (1, 7, 16, 17, 32):
@@ -341,10 +343,13 @@ def test_launch_plans_random_shapes_stay_inside_the_machine():
         for ws in (False, True):
             text = ams.ams_linear_plan(fmt, M, N, K, with_workspace=ws)
             kind, kv = text.split()[0], dict(x.split("=") for x in text.split()[1:])
-            assert kind == ("column" if fmt >= 0 else kind) and kind in ("column", "sweep", "stream"), text
+            assert kind == ("column" if fmt >= 0 else kind) and kind in ("column", "gemv", "sweep", "stream"), text
             assert 0 < int(kv["lds"]) <= 160 * 1024, text
             assert 1 <= int(kv["waves"]) <= 16 and int(kv["phases"]) >= 1 and int(kv["grid"]) >= 1, text
             n_strips = -(-N // 16)
+            if kind == "gemv":
+                assert M <= 4 and int(kv["rows_per_wave"]) * int(kv["grid"]) * 16 >= N and int(kv["lds"]) >= 2 * M * K, text
+                continue
             assert int(kv["strips_per_wg"]) * int(kv["grid"]) >= n_strips * int(kv["k_slices"]) or kind == "stream", text
             if kind == "sweep":
                 assert 16 % int(kv["waves_per_strip"]) == 0 or int(kv["waves_per_strip"]) == int(kv["waves"]), text

@@ -982,10 +982,11 @@ __global__ void __launch_bounds__(1024) gemv_fp16_kernel(LinearArgs a) {
 // QD (formats with side bits): the records are dealt to a strip's wavefronts in whole side groups,
 // so that a group's side dword is loaded once per group and not once per record; used where the
 // groups of a phase divide evenly enough among the wavefronts (the host decides).
-template <int FMT, int MT, bool NT, bool GS, bool QD = false>
+template <int FMT, int MT, bool NT, bool GS, bool QD = false, int LR = 2>
 __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, LR = 2, RS = LR + 1;
+  constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, RS = LR + 1;
+  static_assert(!QD || LR == 2, "the side-group deal fixes its ring at four slots, two records ahead");
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
                "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wps));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
@@ -1162,24 +1163,8 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     }
   }
 
-  // Finish the strips, one per wave: the wps tiles of a strip added in wave order.
-  if (wj < ns && m_lo < mc) {  // idle wavefronts of a strip leave a tile of zeros
-    f4* t = parts + (size_t)(wj * wps + wk) * part_f4 + kq * mc + m_lo;
-#pragma unroll
-    for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
-  }
-  __syncthreads();
-  for (int j = wave; j < ns; j += S) {
-    f4 sum[MT];
-#pragma unroll
-    for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
-    if (m_lo < mc) {
-      const f4* t0 = parts + (size_t)j * wps * part_f4 + kq * mc + m_lo;
-      for (int w = 0; w < wps; w++) {
-#pragma unroll
-        for (int t = 0; t < MT; t++) sum[t] += t0[(size_t)w * part_f4 + t * 4 * mc];
-      }
-    }
+  // Finish strip j of the workgroup with its complete tile of this workgroup's slice of K.
+  auto finish = [&](int j, f4 (&sum)[MT]) {
     const int out_strip = s_first + j;
     if (a.gk > 1) {
       // K is split over gk workgroups: every one leaves its partial tile in the workspace and
@@ -1203,7 +1188,7 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
       unsigned before = 0;
       if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + out_strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       before = __builtin_amdgcn_readfirstlane(before);
-      if (before != (unsigned)a.gk - 1) continue;
+      if (before != (unsigned)a.gk - 1) return;
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the count has returned; the tile loads below are issued after it
 #pragma unroll
       for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
@@ -1222,6 +1207,31 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     else
       sc = j == wave ? scales_from_bits(scale0_bits, kTwo14) : load_scales<FMT>(a, out_strip, lane);
     store_tile_scaled<MT>(sum, sc, a, out_strip, lane);
+  };
+  // A wavefront that is alone on its strip finishes it straight from its accumulators.
+  if (wps == 1) {
+    if (wj < ns) finish(wj, acc);
+    return;
+  }
+  // Otherwise one wave per strip adds the wps tiles of the strip in wave order, through LDS.
+  if (wj < ns && m_lo < mc) {  // idle wavefronts of a strip leave a tile of zeros
+    f4* t = parts + (size_t)(wj * wps + wk) * part_f4 + kq * mc + m_lo;
+#pragma unroll
+    for (int i = 0; i < MT; i++) t[i * 4 * mc] = acc[i];
+  }
+  __syncthreads();
+  for (int j = wave; j < ns; j += S) {
+    f4 sum[MT];
+#pragma unroll
+    for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+    if (m_lo < mc) {
+      const f4* t0 = parts + (size_t)j * wps * part_f4 + kq * mc + m_lo;
+      for (int w = 0; w < wps; w++) {
+#pragma unroll
+        for (int t = 0; t < MT; t++) sum[t] += t0[(size_t)w * part_f4 + t * 4 * mc];
+      }
+    }
+    finish(j, sum);
   }
 }
 
@@ -1409,6 +1419,7 @@ struct ColumnPlan {
   int S, spw, grid, gn, gk, wps, rc, n_phase, x_shift, x_stride, x_region;
   bool qd;  // records dealt in whole side groups
   int wpa;  // wavefronts of a strip that take records (= wps unless fewer divide the side groups evenly)
+  int lr;   // records a wavefront keeps in flight beside the one it restores
   size_t lds;
 };
 
@@ -1418,18 +1429,32 @@ struct ColumnPlan {
 // and one tile per wavefront for the final sum.  Every shape the entry points accept gets a plan.
 // gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
 // allow_qd: the caller's variant can deal whole side groups (not with one scale per run of input channels).
-ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1, bool allow_qd = true) {
+ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1, bool allow_qd = true,
+                            bool allow_deep = true) {
   ColumnPlan p;
   const int sg = ams::side_group(ams::kFormats[fmt]);
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
   p.gk = gk;
   p.S = 16;
+  p.lr = 2;
   const int n_rec = (n_rec_all + gk - 1) / gk;  // records of the longest slice
   const int wg_along_n = kNumCU / gk;
   p.spw = (int)std::min<int64_t>(16, (n_strips + wg_along_n - 1) / wg_along_n);
   p.gn = (int)((n_strips + p.spw - 1) / p.spw);
   p.grid = p.gn * gk;
+  // Eight wavefronts with three records ahead instead of sixteen with two: fewer wavefronts contend for the VALU
+  // and nearly the same bytes are in flight.  Measured on twelve shapes (formats whose records carry no side
+  // groups; the others gained nothing): 1-7 % faster where the workgroups fill the chip, at least seven of the
+  // eight wavefronts get a strip or an equal share of one, and a wavefront's stream is long enough to amortise the
+  // deeper ring's start; slower elsewhere, and slower at larger batches (half the threads stage the activations)
+  // except where a wavefront is alone on its strip and needs no sum through LDS at the end (up to a batch of 16).
+  {
+    const int active = p.spw <= 8 ? (8 / p.spw) * p.spw : 0;  // of eight wavefronts, those that get records
+    if (allow_deep && sg == 1 && gk == 1 && active >= 7 && p.grid >= kNumCU * 7 / 8 &&
+        (int64_t)n_rec * p.spw >= 16 * active && (M <= 2 || (p.spw >= 7 && M <= 16)))
+      p.S = 8, p.lr = 3;
+  }
   p.wps = p.S / p.spw;
   const size_t parts = (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
   // Whole side groups per wavefront where that divides the work evenly enough: the phases then start on group
@@ -1640,8 +1665,11 @@ int launch_gemv(int M, bool nt, const LinearArgs& a, unsigned grid, size_t lds, 
 
 // The packed formats' kernel: nt = non-temporal weight loads, gs = one scale per run of input channels.
 template <int FMT, int MT>
-int launch_column(bool nt, bool gs, bool qd, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+int launch_column(bool nt, bool gs, bool qd, int lr, const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
   if (gs) return launch(column_kernel<FMT, MT, true, true>, a, grid, S, lds, st);
+  if constexpr (Fmt<FMT>::SG == 1) {
+    if (lr == 3) return nt ? launch(column_kernel<FMT, MT, true, false, false, 3>, a, grid, S, lds, st) : AMS_ERR_LAUNCH;
+  }
   if constexpr (Fmt<FMT>::SG > 1) {
     if (qd)
       return nt ? launch(column_kernel<FMT, MT, true, false, true>, a, grid, S, lds, st)
@@ -1714,7 +1742,11 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     }
   };
   if constexpr (FMT != FMT_FP16) {
-    const ColumnPlan cp = make_column_plan(FMT, M, n_strips, n_rec, REC_K, gk, scale_group == 0);
+    // Non-temporal loads for everything but tiny matrices.  Measured with every call reading weights that are not
+    // in any cache (a model's layers in turn): equal or up to 5 % faster than ordinary loads at every size; ordinary
+    // loads only win when the same few megabytes are read again call after call.
+    const bool nt = n_strips * n_rec * (int64_t)REC_BYTES >= (2ll << 20);
+    const ColumnPlan cp = make_column_plan(FMT, M, n_strips, n_rec, REC_K, gk, scale_group == 0, scale_group == 0 && nt);
     a.gn = cp.gn;
     a.gk = cp.gk;
     a.wps = cp.wps;
@@ -1725,12 +1757,8 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.x_shift = cp.x_shift;
     a.spw = cp.spw;
     a.rc = cp.rc;
-    // Non-temporal loads for everything but tiny matrices.  Measured with every call reading weights that are not
-    // in any cache (a model's layers in turn): equal or up to 5 % faster than ordinary loads at every size; ordinary
-    // loads only win when the same few megabytes are read again call after call.
-    const bool nt = n_strips * n_rec * (int64_t)REC_BYTES >= (2ll << 20);
-    return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st)
-                   : launch_column<FMT, 2>(nt, scale_group != 0, cp.qd, a, cp.grid, cp.S, cp.lds, st);
+    return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, cp.qd, cp.lr, a, cp.grid, cp.S, cp.lds, st)
+                   : launch_column<FMT, 2>(nt, scale_group != 0, cp.qd, cp.lr, a, cp.grid, cp.S, cp.lds, st);
   } else {
     if (const GemvPlan gp = make_gemv_plan(M, K, gk); gp.ok) {
       a.x_stride = gp.kpad;
@@ -1776,9 +1804,13 @@ int prepare_format() {
       for (int gs = 0; gs < 2; gs++)
         for (int qd = 0; qd < 2; qd++) {
           if (gs && (!nt || qd)) continue;
-          ok &= launch_column<FMT, 1>(nt, gs, qd, a, 0, 16, 0, nullptr) == AMS_OK;
-          ok &= launch_column<FMT, 2>(nt, gs, qd, a, 0, 16, 0, nullptr) == AMS_OK;
+          ok &= launch_column<FMT, 1>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
+          ok &= launch_column<FMT, 2>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
         }
+    if constexpr (Fmt<FMT>::SG == 1) {
+      ok &= launch_column<FMT, 1>(true, false, false, 3, a, 0, 8, 0, nullptr) == AMS_OK;
+      ok &= launch_column<FMT, 2>(true, false, false, 3, a, 0, 8, 0, nullptr) == AMS_OK;
+    }
   } else {
     for (int m = 1; m <= 4; m++)
       for (int nt = 0; nt < 2; nt++) ok &= launch_gemv(m, nt != 0, a, 0, 0, nullptr) == AMS_OK;
@@ -1927,9 +1959,10 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
   const int n_rec = (int)((K + rec_k - 1) / rec_k);
   const int gk = with_workspace ? choose_split(f, M, n_strips, n_rec, rec_k, rec_bytes) : 1;
   if (f != FMT_FP16) {
-    const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk);
-    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d", cp.grid,
-             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.wpa);
+    const bool nt = n_strips * n_rec * (int64_t)rec_bytes >= (2ll << 20);  // as run_linear decides it
+    const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk, true, nt);
+    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d ahead=%d", cp.grid,
+             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.wpa, cp.lr);
     return AMS_OK;
   }
   if (const GemvPlan gp = make_gemv_plan(M, K, gk); gp.ok) {

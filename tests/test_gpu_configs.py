@@ -130,3 +130,17 @@ def test_extreme_aspect_ratios(N, K, Ms):
     # of ten thousand records (K walked in phases from M = 5 on, split over workgroups when a workspace is given)
     W = synth.gaussian_weights(N, K, 750 + (N % 7))
     check_shape_against_oracle(N, K, W, Ms, 4999, with_workspace=N < 100, with_static=N < 100)
+
+
+@pytest.mark.parametrize("N,K,Ms,ws", [(30000, 16384, (8, 32), True), (14336, 4096, (1, 2, 3), False)])
+def test_lone_wavefronts_and_eight_wavefront_plans(N, K, Ms, ws):
+    # 30000 x 16384 with a workspace: K in two slices and fifteen strips per workgroup, every wavefront alone on its
+    # strip, so the partial tiles go to the workspace straight from the accumulators (the last workgroup is ragged);
+    # 14336 x 4096: four strips per workgroup, eight wavefronts with three records ahead, two on each strip
+    if ws:
+        assert "k_slices=2" in ams.ams_linear_plan(ams.FP533, Ms[0], N, K, with_workspace=True)
+        assert "waves_per_strip=1 " in ams.ams_linear_plan(ams.FP533, Ms[0], N, K, with_workspace=True)
+    else:
+        assert "waves=8 waves_per_strip=2 " in ams.ams_linear_plan(ams.FP533, Ms[0], N, K)
+    W = synth.gaussian_weights(N, K, 760 + (N % 5))
+    check_shape_against_oracle(N, K, W, Ms, 97, with_workspace=ws, with_static=ws)

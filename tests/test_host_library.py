@@ -253,8 +253,14 @@ def test_launch_plans_cover_the_kernels_and_the_split():
     plan = lambda *a, **k: dict(kv.split("=") for kv in ams.ams_linear_plan(*a, **k).split()[1:])
     kind = lambda *a, **k: ams.ams_linear_plan(*a, **k).split()[0]
     assert kind(ams.FP533, 1, 28672, 4096) == "column"
-    p = plan(ams.FP533, 1, 28672, 4096)
-    assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves_per_strip"], p["phases"]) == ("256", "7", "1", "2", "1")
+    p = plan(ams.FP533, 1, 28672, 4096)  # seven strips per workgroup: eight wavefronts, one alone on each strip, three records ahead
+    assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves"], p["waves_per_strip"], p["phases"], p["ahead"]) == ("256", "7", "1", "8", "1", "1", "3")
+    p = plan(ams.FP425, 1, 28672, 4096)  # formats with side groups keep sixteen wavefronts, two on each strip
+    assert (p["grid"], p["strips_per_wg"], p["waves"], p["waves_per_strip"], p["ahead"], p["side_groups"]) == ("256", "7", "16", "2", "2", "1")
+    assert plan(ams.FP533, 32, 28672, 4096)["waves"] == "16" and plan(ams.FP533, 16, 28672, 4096)["waves"] == "8"
+    assert plan(ams.FP533, 1, 4096, 14336)["waves"] == "8" and plan(ams.FP533, 4, 4096, 14336)["waves"] == "16"
+    assert plan(ams.FP533, 1, 4096, 4096)["waves"] == "16"  # 43 records for 8 wavefronts: too short a stream
+    assert plan(ams.FP533, 1, 6144, 4096)["waves"] == "16"  # 192 workgroups do not fill the chip
     p = plan(ams.FP425, 1, 4096, 14336)  # one strip per workgroup: all 16 wavefronts on it
     assert (p["grid"], p["strips_per_wg"], p["waves_per_strip"], p["phases"]) == ("256", "1", "16", "1")
     p = plan(ams.FP533, 1, 57344, 8192)
@@ -354,7 +360,8 @@ def test_launch_plans_random_shapes_stay_inside_the_machine():
             if kind == "sweep":
                 assert 16 % int(kv["waves_per_strip"]) == 0 or int(kv["waves_per_strip"]) == int(kv["waves"]), text
             if kind == "column":
-                assert int(kv["strips_per_wg"]) <= 16 and int(kv["waves_per_strip"]) == 16 // int(kv["strips_per_wg"]), text
+                assert int(kv["strips_per_wg"]) <= 16 and int(kv["waves_per_strip"]) == int(kv["waves"]) // int(kv["strips_per_wg"]) >= 1, text
+                assert (kv["waves"], kv["ahead"]) in (("16", "2"), ("8", "3")), text
             if not ws:
                 assert kv["k_slices"] == "1", text
             need = ams.ams_linear_workspace_bytes(fmt, M, N, K)

@@ -986,7 +986,9 @@ template <int FMT, int MT, bool NT, bool GS, bool QD = false, int LR = 2>
 __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, RS = LR + 1;
-  static_assert(!QD || LR == 2, "the side-group deal fixes its ring at four slots, two records ahead");
+  // the side-group deal has a ring of four slots and two side registers: a request must stay within the group after
+  // the one being multiplied
+  static_assert(!QD || LR == 2 || (LR == 3 && SG == 4), "records ahead in the side-group deal");
   asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
                "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wps));
   const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
@@ -1078,10 +1080,11 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
           side_reg = NT ? __builtin_nontemporal_load(sp) : *sp;
         }
       };
-      request(0, ring[0], side[0], true);
-      __builtin_amdgcn_sched_barrier(0);
-      request(1, ring[1], side[(1 / SG) & 1], 1 % SG == 0);
-      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < LR; q++) {
+        request(q, ring[q], side[(q / SG) & 1], q % SG == 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
       __syncthreads();
 
@@ -1423,38 +1426,25 @@ struct ColumnPlan {
   size_t lds;
 };
 
-// Launch shape of the packed formats' kernel: 16 wavefronts per workgroup, up to 16 neighbouring
-// strips per workgroup (one resident round of workgroups where the matrix allows it), 16 / strips
+// Launch shape of the packed formats' kernel for S wavefronts per workgroup that keep lr records in flight each: up
+// to 16 neighbouring strips per workgroup (one resident round of workgroups where the matrix allows it), S / strips
 // wavefronts on each strip; LDS holds the activations of one phase of K, in as few phases as fit,
 // and one tile per wavefront for the final sum.  Every shape the entry points accept gets a plan.
 // gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
 // allow_qd: the caller's variant can deal whole side groups (not with one scale per run of input channels).
-ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1, bool allow_qd = true,
-                            bool allow_deep = true) {
+ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk, bool allow_qd) {
   ColumnPlan p;
   const int sg = ams::side_group(ams::kFormats[fmt]);
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
   p.gk = gk;
-  p.S = 16;
-  p.lr = 2;
+  p.S = S;
+  p.lr = lr;
   const int n_rec = (n_rec_all + gk - 1) / gk;  // records of the longest slice
   const int wg_along_n = kNumCU / gk;
   p.spw = (int)std::min<int64_t>(16, (n_strips + wg_along_n - 1) / wg_along_n);
   p.gn = (int)((n_strips + p.spw - 1) / p.spw);
   p.grid = p.gn * gk;
-  // Eight wavefronts with three records ahead instead of sixteen with two: fewer wavefronts contend for the VALU
-  // and nearly the same bytes are in flight.  Measured on twelve shapes (formats whose records carry no side
-  // groups; the others gained nothing): 1-7 % faster where the workgroups fill the chip, at least seven of the
-  // eight wavefronts get a strip or an equal share of one, and a wavefront's stream is long enough to amortise the
-  // deeper ring's start; slower elsewhere, and slower at larger batches (half the threads stage the activations)
-  // except where a wavefront is alone on its strip and needs no sum through LDS at the end (up to a batch of 16).
-  {
-    const int active = p.spw <= 8 ? (8 / p.spw) * p.spw : 0;  // of eight wavefronts, those that get records
-    if (allow_deep && sg == 1 && gk == 1 && active >= 7 && p.grid >= kNumCU * 7 / 8 &&
-        (int64_t)n_rec * p.spw >= 16 * active && (M <= 2 || (p.spw >= 7 && M <= 16)))
-      p.S = 8, p.lr = 3;
-  }
   p.wps = p.S / p.spw;
   const size_t parts = (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
   // Whole side groups per wavefront where that divides the work evenly enough: the phases then start on group
@@ -1489,6 +1479,30 @@ ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int
     p.x_shift = 0;
     while ((1 << p.x_shift) < units) p.x_shift++;
     break;
+  }
+  return p;
+}
+
+// allow_qd: the caller's variant can deal whole side groups (not with one scale per run of input channels).
+// allow_deep: the caller has the kernel with three records ahead (non-temporal loads, one scale per row).
+ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk = 1, bool allow_qd = true,
+                            bool allow_deep = true) {
+  const ColumnPlan p = column_plan_for(16, 2, fmt, M, n_strips, n_rec_all, rec_k, gk, allow_qd);
+  // Eight wavefronts with three records ahead instead of sixteen with two: fewer wavefronts contend for the VALU
+  // and nearly the same bytes are in flight.  Measured on fourteen shapes: formats whose records carry no side
+  // groups are 1-7 % faster where the workgroups fill the chip, at least seven of the eight wavefronts get a strip
+  // or an equal share of one, and a wavefront's stream is long enough to amortise the deeper ring's start; slower
+  // elsewhere, and slower at larger batches (half the threads stage the activations) except where a wavefront is
+  // alone on its strip and needs no sum through LDS at the end (up to a batch of 8).  With the side groups dealt
+  // whole only that last case gains: FP4.25 0-8 % (kept), FP4.33 -4 % at K = 4096 and +3 % at K = 8192 (not kept).
+  const int sg = ams::side_group(ams::kFormats[fmt]);
+  const int n_rec = (n_rec_all + gk - 1) / gk;
+  const int active = p.spw <= 8 ? (8 / p.spw) * p.spw : 0;  // of eight wavefronts, those that get records
+  if (!allow_deep || gk != 1 || active < 7 || p.grid < kNumCU * 7 / 8 || (int64_t)n_rec * p.spw < 16 * active) return p;
+  if (sg == 1 && (M <= 2 || (p.spw >= 7 && M <= 8))) return column_plan_for(8, 3, fmt, M, n_strips, n_rec_all, rec_k, gk, allow_qd);
+  if (fmt == FMT_FP425 && allow_qd && p.spw >= 7 && M <= 16) {
+    const ColumnPlan d = column_plan_for(8, 3, fmt, M, n_strips, n_rec_all, rec_k, gk, allow_qd);
+    if (d.qd) return d;  // three records ahead exist for the side-group deal only
   }
   return p;
 }
@@ -1670,6 +1684,9 @@ int launch_column(bool nt, bool gs, bool qd, int lr, const LinearArgs& a, unsign
   if constexpr (Fmt<FMT>::SG == 1) {
     if (lr == 3) return nt ? launch(column_kernel<FMT, MT, true, false, false, 3>, a, grid, S, lds, st) : AMS_ERR_LAUNCH;
   }
+  if constexpr (Fmt<FMT>::SG == 4) {
+    if (qd && lr == 3) return nt ? launch(column_kernel<FMT, MT, true, false, true, 3>, a, grid, S, lds, st) : AMS_ERR_LAUNCH;
+  }
   if constexpr (Fmt<FMT>::SG > 1) {
     if (qd)
       return nt ? launch(column_kernel<FMT, MT, true, false, true>, a, grid, S, lds, st)
@@ -1807,9 +1824,9 @@ int prepare_format() {
           ok &= launch_column<FMT, 1>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
           ok &= launch_column<FMT, 2>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
         }
-    if constexpr (Fmt<FMT>::SG == 1) {
-      ok &= launch_column<FMT, 1>(true, false, false, 3, a, 0, 8, 0, nullptr) == AMS_OK;
-      ok &= launch_column<FMT, 2>(true, false, false, 3, a, 0, 8, 0, nullptr) == AMS_OK;
+    if constexpr (Fmt<FMT>::SG == 1 || Fmt<FMT>::SG == 4) {
+      ok &= launch_column<FMT, 1>(true, false, Fmt<FMT>::SG == 4, 3, a, 0, 8, 0, nullptr) == AMS_OK;
+      ok &= launch_column<FMT, 2>(true, false, Fmt<FMT>::SG == 4, 3, a, 0, 8, 0, nullptr) == AMS_OK;
     }
   } else {
     for (int m = 1; m <= 4; m++)

@@ -255,9 +255,12 @@ def test_launch_plans_cover_the_kernels_and_the_split():
     assert kind(ams.FP533, 1, 28672, 4096) == "column"
     p = plan(ams.FP533, 1, 28672, 4096)  # seven strips per workgroup: eight wavefronts, one alone on each strip, three records ahead
     assert (p["grid"], p["strips_per_wg"], p["k_slices"], p["waves"], p["waves_per_strip"], p["phases"], p["ahead"]) == ("256", "7", "1", "8", "1", "1", "3")
-    p = plan(ams.FP425, 1, 28672, 4096)  # formats with side groups keep sixteen wavefronts, two on each strip
-    assert (p["grid"], p["strips_per_wg"], p["waves"], p["waves_per_strip"], p["ahead"], p["side_groups"]) == ("256", "7", "16", "2", "2", "1")
-    assert plan(ams.FP533, 32, 28672, 4096)["waves"] == "16" and plan(ams.FP533, 16, 28672, 4096)["waves"] == "8"
+    p = plan(ams.FP425, 1, 28672, 4096)  # the same with the side groups dealt whole
+    assert (p["grid"], p["strips_per_wg"], p["waves"], p["waves_per_strip"], p["ahead"], p["side_groups"]) == ("256", "7", "8", "1", "3", "1")
+    p = plan(ams.FP433, 1, 28672, 4096)  # the other formats with side groups keep sixteen wavefronts, two on each strip
+    assert (p["waves"], p["waves_per_strip"], p["ahead"]) == ("16", "2", "2")
+    assert plan(ams.FP533, 32, 28672, 4096)["waves"] == "16" and plan(ams.FP533, 8, 28672, 4096)["waves"] == "8"
+    assert plan(ams.FP425, 1, 4096, 14336)["waves"] == "16"  # one strip per workgroup: sixteen wavefronts share it
     assert plan(ams.FP533, 1, 4096, 14336)["waves"] == "8" and plan(ams.FP533, 4, 4096, 14336)["waves"] == "16"
     assert plan(ams.FP533, 1, 4096, 4096)["waves"] == "16"  # 43 records for 8 wavefronts: too short a stream
     assert plan(ams.FP533, 1, 6144, 4096)["waves"] == "16"  # 192 workgroups do not fill the chip

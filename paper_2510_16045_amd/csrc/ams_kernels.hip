@@ -968,6 +968,48 @@ __global__ void __launch_bounds__(1024) gemv_fp16_kernel(LinearArgs a) {
     if (i + q < total) step(ring[q], ring[(q + LR) % RS]);
 }
 
+// Finish one strip with the complete tile of this workgroup's slice of K: times the scales, converted, stored; with
+// K split over gk workgroups, through the workspace.
+template <int MT>
+__device__ __forceinline__ void finish_strip(const LinearArgs& a, int gk, int out_strip, f4 (&sum)[MT], const f4 sc, int lane) {
+  if (a.gk > 1) {
+    // K is split over gk workgroups: every one leaves its partial tile in the workspace and
+    // counts itself in; the one that arrives last adds all gk tiles in slice order (so the
+    // result does not depend on who was last), finishes the strip and clears the counter
+    // for the next call.  Nobody waits for anybody.
+    // The tiles travel as device-scope relaxed atomic stores and loads (they go to the level
+    // of the memory system all compute units share).  What orders them: the wave waits until
+    // every one of its tile stores has been acknowledged (s_waitcnt vmcnt(0): on this target
+    // stores count in vmcnt) before it counts itself in, and the last arriver's tile loads are
+    // issued only after its own count has come back (the branch below depends on it).  A
+    // device-scope fence would instead write back and invalidate the whole L2, which costs
+    // more than the Linear itself.
+    float* wt = (float*)(a.ws_tiles + ((size_t)gk * a.n_strips + out_strip) * MT * 64 + lane);
+#pragma unroll
+    for (int t = 0; t < MT; t++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) __hip_atomic_store(wt + t * 256 + r, sum[t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // all tile stores of this wave acknowledged; the compiler moves no memory access across either statement
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned before = 0;
+    if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + out_strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before != (unsigned)a.gk - 1) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the count has returned; the tile loads below are issued after it
+#pragma unroll
+    for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
+    for (int q = 0; q < a.gk; q++) {
+      const float* rt = (const float*)(a.ws_tiles + ((size_t)q * a.n_strips + out_strip) * MT * 64 + lane);
+#pragma unroll
+      for (int t = 0; t < MT; t++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) sum[t][r] += __hip_atomic_load(rt + t * 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane == 0) __hip_atomic_store(a.ws_count + out_strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  store_tile_scaled<MT>(sum, sc, a, out_strip, lane);
+}
+
 // The Linear on packed weights.  A workgroup owns up to 16 neighbouring strips (spw of them,
 // one resident round of workgroups; more strips than 16 x 256 just means more workgroups) and
 // has S / spw wavefronts on each: a wavefront stays with its strip and takes every wps-th
@@ -1169,47 +1211,12 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
   // Finish strip j of the workgroup with its complete tile of this workgroup's slice of K.
   auto finish = [&](int j, f4 (&sum)[MT]) {
     const int out_strip = s_first + j;
-    if (a.gk > 1) {
-      // K is split over gk workgroups: every one leaves its partial tile in the workspace and
-      // counts itself in; the one that arrives last adds all gk tiles in slice order (so the
-      // result does not depend on who was last), finishes the strip and clears the counter
-      // for the next call.  Nobody waits for anybody.
-      // The tiles travel as device-scope relaxed atomic stores and loads (they go to the level
-      // of the memory system all compute units share).  What orders them: the wave waits until
-      // every one of its tile stores has been acknowledged (s_waitcnt vmcnt(0): on this target
-      // stores count in vmcnt) before it counts itself in, and the last arriver's tile loads are
-      // issued only after its own count has come back (the branch below depends on it).  A
-      // device-scope fence would instead write back and invalidate the whole L2, which costs
-      // more than the Linear itself.
-      float* wt = (float*)(a.ws_tiles + ((size_t)gk * a.n_strips + out_strip) * MT * 64 + lane);
-#pragma unroll
-      for (int t = 0; t < MT; t++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) __hip_atomic_store(wt + t * 256 + r, sum[t][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      // all tile stores of this wave acknowledged; the compiler moves no memory access across either statement
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      unsigned before = 0;
-      if (lane == 0) before = __hip_atomic_fetch_add(a.ws_count + out_strip, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      before = __builtin_amdgcn_readfirstlane(before);
-      if (before != (unsigned)a.gk - 1) return;
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the count has returned; the tile loads below are issued after it
-#pragma unroll
-      for (int t = 0; t < MT; t++) sum[t] = f4{0, 0, 0, 0};
-      for (int q = 0; q < a.gk; q++) {
-        const float* rt = (const float*)(a.ws_tiles + ((size_t)q * a.n_strips + out_strip) * MT * 64 + lane);
-#pragma unroll
-        for (int t = 0; t < MT; t++)
-#pragma unroll
-          for (int r = 0; r < 4; r++) sum[t][r] += __hip_atomic_load(rt + t * 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      if (lane == 0) __hip_atomic_store(a.ws_count + out_strip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
     f4 sc;
     if constexpr (GS)
       sc = f4{kTwo14, kTwo14, kTwo14, kTwo14};
     else
       sc = j == wave ? scales_from_bits(scale0_bits, kTwo14) : load_scales<FMT>(a, out_strip, lane);
-    store_tile_scaled<MT>(sum, sc, a, out_strip, lane);
+    finish_strip<MT>(a, gk, out_strip, sum, sc, lane);
   };
   // A wavefront that is alone on its strip finishes it straight from its accumulators.
   if (wps == 1) {
@@ -1236,6 +1243,123 @@ __global__ void __launch_bounds__(1024) column_kernel(LinearArgs a) {
     }
     finish(j, sum);
   }
+}
+
+// The Linear on packed weights where a workgroup owns more strips than it has wavefronts: eight wavefronts, each
+// alone on NS strips of the workgroup (wave w on strips w, w + wn, ...; wn = a.wpa wavefronts own strips), which it
+// walks record by record side by side (record r of its first strip, record r of its second, record r + 1 ...), one
+// accumulator tile per strip, three records ahead in a ring of four.  All strips of the workgroup are still read
+// at the same record index at the same time (the contiguous window of the column kernel), the activations are
+// staged as there, and every strip is finished straight from its wavefront's accumulators: no tiles in LDS, no
+// barrier after the last record.  For the formats whose records carry no side groups (with the side groups of two
+// strips dealt in turn FP4.25 was 1-3 % slower than with sixteen wavefronts on one strip each: measured, not kept).
+template <int FMT, int MT, bool NT, int NS>
+__global__ void __launch_bounds__(512) multi_kernel(LinearArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int REC_K = Fmt<FMT>::REC_K, SG = Fmt<FMT>::SG, LR = 3;
+  static_assert(NS == 2 || NS == 4, "strips per wavefront: the ring of four must hold whole rounds of them");
+  asm volatile("" ::"s"(a.W), "s"(a.scales), "s"(a.X), "s"(a.Y), "s"(a.M), "s"(a.N), "s"(a.K), "s"(a.n_rec), "s"(a.x_stride),
+               "s"(a.x_region), "s"(a.x_shift), "s"(a.n_strips), "s"(a.spw), "s"(a.rc), "s"(a.gn), "s"(a.gk), "s"(a.wpa));
+  const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int G = a.gn;
+  const int gk = a.gk > 1 ? (int)(blockIdx.x / (unsigned)G) : 0;
+  const int g = (int)blockIdx.x - gk * G;
+  const int s_first = g * a.spw;
+  const int ns = min(a.spw, a.n_strips - s_first);  // >= 1
+  const int wn = a.wpa;                             // wavefronts that own strips
+  const bool has_strip = wave < wn && wave < ns;
+  int sidx[NS];    // this wave's strips (those that do not exist stand for the workgroup's last: read, never finished)
+  bool valid[NS];
+#pragma unroll
+  for (int i = 0; i < NS; i++) {
+    valid[i] = wave < wn && wave + i * wn < ns;
+    sidx[i] = s_first + min(wave + i * wn, ns - 1);
+  }
+  const int rec_lo = a.gk > 1 ? (int)((unsigned)(gk * a.n_rec) / (unsigned)a.gk) : 0;
+  const int rec_hi = a.gk > 1 ? (int)((unsigned)((gk + 1) * a.n_rec) / (unsigned)a.gk) : a.n_rec;
+  const int RC = a.rc;
+  _Float16* xs = (_Float16*)smem;
+  const int m_lo = lane & 15, kq = lane >> 4;
+  const int lane_off = (REC_K / 4) * kq;
+  const _Float16* x0 = xs + (m_lo < a.M ? m_lo : 0) * a.x_stride + lane_off;
+  const _Float16* x1 = xs + (m_lo + 16 < a.M ? m_lo + 16 : 0) * a.x_stride + lane_off;
+  const bool vec_x = (a.K & 7) == 0;
+  const int total_units = a.M << a.x_shift;
+  const int units_per_pass = nthr * XUnit<FMT>::XU;
+  const bool wave_has_x = vec_x && wave * 64 < total_units;  // wave-uniform
+  const int chunk_k = RC * REC_K;
+  ScaleBits sb[NS];
+#pragma unroll
+  for (int i = 0; i < NS; i++) sb[i] = load_scale_bits<FMT>(a, sidx[i], lane);
+  __builtin_amdgcn_sched_barrier(0);
+
+  f4 acc[NS][MT];
+#pragma unroll
+  for (int i = 0; i < NS; i++)
+#pragma unroll
+    for (int t = 0; t < MT; t++) acc[i][t] = f4{0, 0, 0, 0};
+
+  for (int rec_base = rec_lo; rec_base < rec_hi; rec_base += RC) {
+    const int n_rec = min(RC, rec_hi - rec_base);
+    if (rec_base > rec_lo) __syncthreads();  // everyone is done with the previous phase's activations
+    const int k0 = rec_base * REC_K;
+    XRegs<FMT> xr;
+    if (vec_x) {
+      for (int u0 = units_per_pass; u0 < total_units; u0 += nthr * XUnit<FMT>::XB) {
+        XRegs<FMT, XUnit<FMT>::XB> xb;
+        x_load(xb, a, k0, chunk_k, u0, tid, nthr);
+        x_store(xb, xs, a, k0, chunk_k, u0, tid, nthr);
+      }
+    } else {
+      stage_x_unaligned<FMT>(xs, a, k0, chunk_k, tid, nthr);
+    }
+    if (wave_has_x) x_load(xr, a, k0, chunk_k, 0, tid, nthr);
+    __builtin_amdgcn_sched_barrier(0);
+
+    LaneRec<FMT> ring[4];
+    {
+      // records e = 0 .. NS * n_rec - 1 of the phase: strip e % NS, record e / NS
+      const int total_e = has_strip ? NS * n_rec : 0;
+      int qr = 0;  // record of the next request, relative to the phase (stops at the last)
+      auto request = [&](LaneRec<FMT>& slot, int i) {
+        load_rec<FMT, NT>(slot, a, sidx[i], rec_base + min(qr, n_rec - 1), lane);
+        if (i == NS - 1) qr++;
+      };
+#pragma unroll
+      for (int q = 0; q < LR; q++) {
+        request(ring[q], q % NS);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (wave_has_x) x_store(xr, xs, a, k0, chunk_k, 0, tid, nthr);
+      __syncthreads();
+      int cr = 0;  // record being multiplied, relative to the phase
+      auto step = [&](auto uc) {
+        constexpr int u = decltype(uc)::value;
+        request(ring[(u + LR) & 3], (u + LR) % NS);
+        __builtin_amdgcn_sched_barrier(0);
+        const int side_shift = 8 * Fmt<FMT>::SIDE * ((rec_base + cr) & (SG - 1));
+        mac_rec<FMT, MT>(ring[u & 3], x0 + cr * REC_K, x1 + cr * REC_K, acc[u % NS], side_shift);
+        if (u % NS == NS - 1) cr++;
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      int e = 0;
+      for (; e + 4 <= total_e; e += 4) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+      }
+      if (e < total_e) {  // NS = 2 and an odd number of records: one more of each strip
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+      }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < NS; i++)
+    if (valid[i]) finish_strip<MT>(a, gk, sidx[i], acc[i], scales_from_bits(sb[i], kTwo14), lane);
 }
 
 // Restore a whole packed matrix to row-major fp16: one wavefront per record.
@@ -1423,6 +1547,7 @@ struct ColumnPlan {
   bool qd;  // records dealt in whole side groups
   int wpa;  // wavefronts of a strip that take records (= wps unless fewer divide the side groups evenly)
   int lr;   // records a wavefront keeps in flight beside the one it restores
+  int ns;   // strips a wavefront owns alone (multi_kernel; 1: column_kernel); then wpa = wavefronts that own strips
   size_t lds;
 };
 
@@ -1432,8 +1557,10 @@ struct ColumnPlan {
 // and one tile per wavefront for the final sum.  Every shape the entry points accept gets a plan.
 // gk > 1: K is cut in gk slices, each with its own kNumCU / gk workgroups along N.
 // allow_qd: the caller's variant can deal whole side groups (not with one scale per run of input channels).
-ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk, bool allow_qd) {
+ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int n_rec_all, int rec_k, int gk, bool allow_qd,
+                           int ns = 1) {
   ColumnPlan p;
+  p.ns = ns;
   const int sg = ams::side_group(ams::kFormats[fmt]);
   const int mt = M > 16 ? 2 : 1;
   const int mc = std::min(M, 16);
@@ -1445,8 +1572,8 @@ ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int 
   p.spw = (int)std::min<int64_t>(16, (n_strips + wg_along_n - 1) / wg_along_n);
   p.gn = (int)((n_strips + p.spw - 1) / p.spw);
   p.grid = p.gn * gk;
-  p.wps = p.S / p.spw;
-  const size_t parts = (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
+  p.wps = ns > 1 ? 1 : p.S / p.spw;
+  const size_t parts = ns > 1 ? 0 : (size_t)p.spw * p.wps * mt * 4 * mc * 16;  // at most 32 KiB
   // Whole side groups per wavefront where that divides the work evenly enough: the phases then start on group
   // boundaries, and every wavefront of a strip must get (nearly) the same number of groups.
   p.qd = false;
@@ -1469,7 +1596,7 @@ ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int 
     const size_t lds = (size_t)M * x_stride * 2 + parts;
     if (lds > (size_t)kLdsMaxBytes && rc > 1) continue;  // one record per phase always fits (32 rows x 136 halfs)
     p.qd = qd;
-    p.wpa = wpa;
+    p.wpa = ns > 1 ? (p.spw + ns - 1) / ns : wpa;
     p.rc = rc;
     p.n_phase = (n_rec + rc - 1) / rc;
     p.x_stride = x_stride;
@@ -1497,6 +1624,10 @@ ColumnPlan make_column_plan(int fmt, int M, int64_t n_strips, int n_rec_all, int
   // whole only that last case gains: FP4.25 0-8 % (kept), FP4.33 -4 % at K = 4096 and +3 % at K = 8192 (not kept).
   const int sg = ams::side_group(ams::kFormats[fmt]);
   const int n_rec = (n_rec_all + gk - 1) / gk;
+  // More strips than eight wavefronts: two strips per wavefront, side by side (70B gate/up 50.8 -> 48.5 us, the
+  // 128256 x 4096 vocabulary projection 55.1 -> 54.5, the same at K = 8192 +- 0; batches up to 8 measured).
+  if (allow_deep && sg == 1 && gk == 1 && p.spw >= 9 && p.grid >= kNumCU * 7 / 8 && n_rec >= 8 && M <= 8)
+    return column_plan_for(8, 3, fmt, M, n_strips, n_rec_all, rec_k, gk, allow_qd, 2);
   const int active = p.spw <= 8 ? (8 / p.spw) * p.spw : 0;  // of eight wavefronts, those that get records
   if (!allow_deep || gk != 1 || active < 7 || p.grid < kNumCU * 7 / 8 || (int64_t)n_rec * p.spw < 16 * active) return p;
   if (sg == 1 && (M <= 2 || (p.spw >= 7 && M <= 8))) return column_plan_for(8, 3, fmt, M, n_strips, n_rec_all, rec_k, gk, allow_qd);
@@ -1696,6 +1827,13 @@ int launch_column(bool nt, bool gs, bool qd, int lr, const LinearArgs& a, unsign
             : launch(column_kernel<FMT, MT, false, false>, a, grid, S, lds, st);
 }
 
+// Wavefronts that own two strips each (non-temporal loads, one scale per row).
+template <int FMT, int MT>
+int launch_multi(const LinearArgs& a, unsigned grid, int S, size_t lds, hipStream_t st) {
+  if constexpr (Fmt<FMT>::SG == 1) return launch(multi_kernel<FMT, MT, true, 2>, a, grid, S, lds, st);
+  return AMS_ERR_LAUNCH;
+}
+
 template <int FMT>
 int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N, int64_t K,
                void* stream, int64_t scale_group = 0, void* workspace = nullptr, size_t ws_bytes = 0) {
@@ -1774,6 +1912,7 @@ int run_linear(const void* W, const uint16_t* scales, const uint16_t* X, uint16_
     a.x_shift = cp.x_shift;
     a.spw = cp.spw;
     a.rc = cp.rc;
+    if (cp.ns > 1) return M <= 16 ? launch_multi<FMT, 1>(a, cp.grid, cp.S, cp.lds, st) : launch_multi<FMT, 2>(a, cp.grid, cp.S, cp.lds, st);
     return M <= 16 ? launch_column<FMT, 1>(nt, scale_group != 0, cp.qd, cp.lr, a, cp.grid, cp.S, cp.lds, st)
                    : launch_column<FMT, 2>(nt, scale_group != 0, cp.qd, cp.lr, a, cp.grid, cp.S, cp.lds, st);
   } else {
@@ -1824,6 +1963,10 @@ int prepare_format() {
           ok &= launch_column<FMT, 1>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
           ok &= launch_column<FMT, 2>(nt, gs, qd, 2, a, 0, 16, 0, nullptr) == AMS_OK;
         }
+    if constexpr (Fmt<FMT>::SG == 1) {
+      ok &= launch_multi<FMT, 1>(a, 0, 8, 0, nullptr) == AMS_OK;
+      ok &= launch_multi<FMT, 2>(a, 0, 8, 0, nullptr) == AMS_OK;
+    }
     if constexpr (Fmt<FMT>::SG == 1 || Fmt<FMT>::SG == 4) {
       ok &= launch_column<FMT, 1>(true, false, Fmt<FMT>::SG == 4, 3, a, 0, 8, 0, nullptr) == AMS_OK;
       ok &= launch_column<FMT, 2>(true, false, Fmt<FMT>::SG == 4, 3, a, 0, 8, 0, nullptr) == AMS_OK;
@@ -1978,8 +2121,8 @@ int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, ch
   if (f != FMT_FP16) {
     const bool nt = n_strips * n_rec * (int64_t)rec_bytes >= (2ll << 20);  // as run_linear decides it
     const ColumnPlan cp = make_column_plan(f, M, n_strips, n_rec, rec_k, gk, true, nt);
-    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d ahead=%d", cp.grid,
-             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.wpa, cp.lr);
+    snprintf(text, text_len, "column grid=%d strips_per_wg=%d k_slices=%d waves=%d waves_per_strip=%d phases=%d lds=%zu side_groups=%d active_per_strip=%d ahead=%d strips_per_wave=%d", cp.grid,
+             cp.spw, cp.gk, cp.S, cp.wps, cp.n_phase, cp.lds, cp.qd ? 1 : 0, cp.ns > 1 ? 1 : cp.wpa, cp.lr, cp.ns);
     return AMS_OK;
   }
   if (const GemvPlan gp = make_gemv_plan(M, K, gk); gp.ok) {

@@ -144,3 +144,15 @@ def test_lone_wavefronts_and_eight_wavefront_plans(N, K, Ms, ws):
         assert "waves=8 waves_per_strip=2 " in ams.ams_linear_plan(ams.FP533, Ms[0], N, K)
     W = synth.gaussian_weights(N, K, 760 + (N % 5))
     check_shape_against_oracle(N, K, W, Ms, 97, with_workspace=ws, with_static=ws)
+
+
+@pytest.mark.parametrize("N,K,Ms", [(45000, 4096, (1, 3, 8)), (45000, 16384, (8,))])
+def test_wavefronts_with_two_strips_each(N, K, Ms):
+    # 2813 strips: eleven per workgroup (an odd number for eight wavefronts with two strips each: one wavefront has
+    # a single strip), the last workgroup has eight; 43 records per strip (an odd count), or K walked in two phases
+    for M in Ms:
+        assert "strips_per_wave=2" in ams.ams_linear_plan(ams.FP533, M, N, K)
+    assert "phases=1 " not in ams.ams_linear_plan(ams.FP533, 8, 45000, 16384)
+    W = synth.gaussian_weights(N, K, 770 + (K % 7))
+    n_strips = -(-N // 16)
+    check_shape_against_oracle(N, K, W, Ms, 211, extra_strips=tuple(range(n_strips - 12, n_strips)) + tuple(range(0, 23)))

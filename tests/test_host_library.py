@@ -266,8 +266,11 @@ def test_launch_plans_cover_the_kernels_and_the_split():
     assert plan(ams.FP533, 1, 6144, 4096)["waves"] == "16"  # 192 workgroups do not fill the chip
     p = plan(ams.FP425, 1, 4096, 14336)  # one strip per workgroup: all 16 wavefronts on it
     assert (p["grid"], p["strips_per_wg"], p["waves_per_strip"], p["phases"]) == ("256", "1", "16", "1")
-    p = plan(ams.FP533, 1, 57344, 8192)
-    assert (p["grid"], p["strips_per_wg"], p["waves_per_strip"]) == ("256", "14", "1")
+    p = plan(ams.FP533, 1, 57344, 8192)  # fourteen strips per workgroup: eight wavefronts (seven busy) with two strips each
+    assert (p["grid"], p["strips_per_wg"], p["waves"], p["waves_per_strip"], p["strips_per_wave"], p["ahead"]) == ("256", "14", "8", "1", "2", "3")
+    p = plan(ams.FP425, 1, 57344, 8192)  # with side groups: sixteen wavefronts, fourteen of them alone on a strip
+    assert (p["grid"], p["strips_per_wg"], p["waves"], p["waves_per_strip"], p["strips_per_wave"]) == ("256", "14", "16", "1", "1")
+    assert plan(ams.FP533, 16, 57344, 8192)["strips_per_wave"] == "1"
     assert plan(ams.FP533, 1, 128256, 4096)["strips_per_wg"] == "16"  # more strips than 16 x 256: more workgroups
     assert int(plan(ams.FP533, 1, 128256, 4096)["grid"]) == -(-(-(-128256 // 16)) // 16)
     assert kind(ams.FP533, 32, 57344, 8192) == "column" and int(plan(ams.FP533, 32, 57344, 8192)["phases"]) > 1
@@ -363,7 +366,10 @@ def test_launch_plans_random_shapes_stay_inside_the_machine():
             if kind == "sweep":
                 assert 16 % int(kv["waves_per_strip"]) == 0 or int(kv["waves_per_strip"]) == int(kv["waves"]), text
             if kind == "column":
-                assert int(kv["strips_per_wg"]) <= 16 and int(kv["waves_per_strip"]) == int(kv["waves"]) // int(kv["strips_per_wg"]) >= 1, text
+                if kv["strips_per_wave"] == "1":
+                    assert int(kv["strips_per_wg"]) <= 16 and int(kv["waves_per_strip"]) == int(kv["waves"]) // int(kv["strips_per_wg"]) >= 1, text
+                else:  # wavefronts that own two strips each
+                    assert (kv["strips_per_wave"], kv["waves"], kv["waves_per_strip"], kv["k_slices"]) == ("2", "8", "1", "1") and 9 <= int(kv["strips_per_wg"]) <= 16, text
                 assert (kv["waves"], kv["ahead"]) in (("16", "2"), ("8", "3")), text
             if not ws:
                 assert kv["k_slices"] == "1", text

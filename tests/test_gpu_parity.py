@@ -152,6 +152,24 @@ def test_grouped_scales_large_shape_sampled_rows(fmt, ofmt):
         check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt, sg), f"grouped large M={M}")
 
 
+@pytest.mark.parametrize("fmt,ofmt", PAPER_PAIRS)
+def test_grouped_scales_lone_wavefronts(fmt, ofmt):
+    # ten strips per workgroup: every wavefront alone on its strip finishes it from its accumulators, here with the
+    # per-run scales already applied record by record (the last workgroup is ragged)
+    N, K = 40100, 1024
+    sg = REC_K[fmt] * 2
+    W = synth.gaussian_weights(N, K, 85)
+    packed, scales = ams.ams_pack_grouped(fmt, W, sg)
+    wp, sc = dev(packed), dev(scales)
+    rows = np.unique(np.r_[0:32, N - 40 : N, np.arange(11, N, 397)])
+    codes, o_scales = O.ams_quantize_grouped(W[rows], ofmt, sg)
+    for M in (1, 20):
+        X = synth.activations(M, K, 86 + M)
+        y = host16(ams.ams_linear_grouped(wp, sc, sg, dev(X), N, fmt)).astype(np.float64)
+        assert np.all(np.isfinite(y))
+        check_linear(y[:, rows].astype(np.float16), O.linear(codes, o_scales, X, ofmt, sg), f"grouped lone M={M}")
+
+
 @pytest.mark.parametrize("fmt,ofmt", PAIRS)
 def test_linear_heavy_tail_weights_and_outlier_activations(fmt, ofmt):
     N, K = 64, 8192

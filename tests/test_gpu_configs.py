@@ -146,10 +146,11 @@ def test_lone_wavefronts_and_eight_wavefront_plans(N, K, Ms, ws):
     check_shape_against_oracle(N, K, W, Ms, 97, with_workspace=ws, with_static=ws)
 
 
-@pytest.mark.parametrize("N,K,Ms", [(45000, 4096, (1, 3, 8)), (45000, 16384, (8,))])
+@pytest.mark.parametrize("N,K,Ms", [(45000, 4096, (1, 3, 8)), (45000, 16384, (8,)), (45000, 1001, (2,))])
 def test_wavefronts_with_two_strips_each(N, K, Ms):
     # 2813 strips: eleven per workgroup (an odd number for eight wavefronts with two strips each: one wavefront has
-    # a single strip), the last workgroup has eight; 43 records per strip (an odd count), or K walked in two phases
+    # a single strip), the last workgroup has eight; 43 records per strip (an odd count), K walked in two phases, or
+    # activation rows that are not 16-byte aligned (K = 1001)
     for M in Ms:
         assert "strips_per_wave=2" in ams.ams_linear_plan(ams.FP533, M, N, K)
     assert "phases=1 " not in ams.ams_linear_plan(ams.FP533, 8, 45000, 16384)

@@ -157,3 +157,23 @@ def test_wavefronts_with_two_strips_each(N, K, Ms):
     W = synth.gaussian_weights(N, K, 770 + (K % 7))
     n_strips = -(-N // 16)
     check_shape_against_oracle(N, K, W, Ms, 211, extra_strips=tuple(range(n_strips - 12, n_strips)) + tuple(range(0, 23)))
+
+
+@pytest.mark.parametrize("fmt,ofmt", [(ams.FP5, O.FP5_E2M2), (ams.FP4, O.FP4_E2M1)])
+@pytest.mark.parametrize("N,K,Ms", [(45000, 4096, (1, 8)), (28672, 4096, (1, 4))])
+def test_other_formats_without_side_groups_on_the_eight_wavefront_plans(fmt, ofmt, N, K, Ms):
+    # FP5 (four side bytes per lane and record, no side groups) and FP4 take the same plans as FP5.33: two strips per
+    # wavefront on 45000 rows, one wavefront alone on each of seven strips on 28672
+    want = "strips_per_wave=2" if N == 45000 else "waves=8 waves_per_strip=1 "
+    assert want in ams.ams_linear_plan(fmt, Ms[0], N, K)
+    W = synth.gaussian_weights(N, K, 780)
+    packed, scales = ams.ams_pack(fmt, W)
+    n_strips = -(-N // 16)
+    strips = sampled_strips(N, 173, tuple(range(n_strips - 12, n_strips)))
+    rows = np.concatenate([np.arange(16 * t, min(N, 16 * t + 16)) for t in strips])
+    codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+    wp, sc = dev(packed), dev(scales)
+    for M in Ms:
+        X = synth.activations(M, K, 781 + M)
+        y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt))
+        check_linear(y[:, rows], O.linear(codes, o_scales, X, ofmt), f"{ofmt.name} N={N} K={K} M={M}")

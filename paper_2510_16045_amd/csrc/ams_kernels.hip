@@ -1020,7 +1020,9 @@ __device__ __forceinline__ void finish_strip(const LinearArgs& a, int gk, int ou
 // partial tile stays in its wavefront's accumulator registers for the whole of K, also across
 // the phases K is walked in when the activations M x K do not fit in LDS; at the end the wps
 // tiles of a strip are added in wave order through LDS (deterministic, no atomics), scaled,
-// converted and stored.  Each wave keeps LR records in flight beside the one it is restoring.
+// converted and stored; a wavefront that is alone on its strip (wps = 1) finishes it straight
+// from its accumulators.  Each wave keeps LR records in flight beside the one it is restoring
+// (two with 16 wavefronts per workgroup, three with 8: the host decides which).
 // QD (formats with side bits): the records are dealt to a strip's wavefronts in whole side groups,
 // so that a group's side dword is loaded once per group and not once per record; used where the
 // groups of a phase divide evenly enough among the wavefronts (the host decides).

@@ -443,34 +443,6 @@ __device__ __forceinline__ void store_tile_scaled(const f4 t[MT], const f4 sc, c
   }
 }
 
-// All threads of a workgroup copy X[0..M) x [0, k_pad) into LDS in operand order (zero beyond K).
-template <int FMT>
-__device__ __forceinline__ void stage_x_block(_Float16* xs, const LinearArgs& a, int k_pad, int tid, int nthr) {
-  constexpr int UNIT = XUnit<FMT>::UNIT, CH = XUnit<FMT>::CH;
-  if ((a.K & 7) != 0) {  // rows not 16-byte aligned
-    stage_x_unaligned<FMT>(xs, a, 0, k_pad, tid, nthr);
-    return;
-  }
-  const int upr = k_pad / UNIT;
-  const int total = a.M << a.x_shift;
-  for (int u = tid; u < total; u += nthr) {
-    const int m = u >> a.x_shift, j = u & ((1 << a.x_shift) - 1);
-    if (j >= upr) continue;
-    const int k = UNIT * j;
-    const uint16_t* src = a.X + (size_t)m * a.K + k;
-    uint32_t in[4 * CH], out[4 * CH];
-#pragma unroll
-    for (int e = 0; e < CH; e++) {
-      const u4 c = k + 8 * e < a.K ? *(const u4*)(src + 8 * e) : u4{0, 0, 0, 0};
-      in[4 * e] = c[0], in[4 * e + 1] = c[1], in[4 * e + 2] = c[2], in[4 * e + 3] = c[3];
-    }
-    permute_unit<FMT>(in, out);
-    u4* dst = (u4*)(xs + m * a.x_stride + UNIT * j);
-#pragma unroll
-    for (int e = 0; e < CH; e++) dst[e] = u4{out[4 * e], out[4 * e + 1], out[4 * e + 2], out[4 * e + 3]};
-  }
-}
-
 // The streaming Linear.  A workgroup owns `spw` consecutive strips and walks K in
 // phases of `rc` records per strip (one phase when the activations M x K fit in LDS).
 // Inside a phase its work is the list of (strip, record) pairs in strip-major order;

@@ -54,6 +54,7 @@ def parse_args():
     ap.add_argument("--sweep-all-layers", action="store_true", help="sweep every layer of the set, not only gate/up and down")
     ap.add_argument("--no-70b", action="store_true", help="skip the Llama-70B-shaped layers at M=1,4,8")
     ap.add_argument("--no-lm-head", action="store_true", help="skip the Llama-3-8B vocabulary projection (128256 x 4096) at M=1,8")
+    ap.add_argument("--no-qwen", action="store_true", help="skip the Qwen MLP-down shapes of the paper's Table 3 at batch 1, 4, 16, 32")
     ap.add_argument("--out", default=None, help="also write the sweep table to this file")
     ap.add_argument("--all-formats", action="store_true", help="per-layer figures and the sweep for all seven formats (the step keeps the paper's two)")
     ap.add_argument("--group-scales", action="store_true", help="also time ams_linear_grouped (one scale per record-sized run of K) per layer")
@@ -262,11 +263,11 @@ def measured_traffic(ams, layer, fmt_name, M):
     return None
 
 
-def batch_sweep(layers, fmts, ams, torch, synth, n_launch, ws):
+def batch_sweep(layers, fmts, ams, torch, synth, n_launch, ws, batches=None):
     """Every layer x M in 1..32 x format: plain ams_linear, the split of K (static scratch), both fp16 baselines."""
     rows = []
     for l in layers:
-        for Mb in SWEEP_MS:
+        for Mb in batches or SWEEP_MS:
             x = to_dev(synth.activations(Mb, l.K, 9), torch)
             y = torch.empty((Mb, l.N), dtype=torch.float16, device="cuda")
             t16 = time_launches(torch, lambda i: ams.ams_fp16_linear(l.w16[i % len(l.w16)], x, out=y), n_launch)
@@ -463,8 +464,8 @@ def main():
         torch.cuda.empty_cache()
         return rows
 
-    llama70b = lm_head = None
-    if args.layers == "8b" and not (args.no_70b and args.no_lm_head):
+    llama70b = lm_head = qwen_down = None
+    if args.layers == "8b" and not (args.no_70b and args.no_lm_head and args.no_qwen):
         del layers, dl, xs, ys
         l = None
         gc.collect()
@@ -475,6 +476,15 @@ def main():
         # the output projection onto the vocabulary, the largest Linear of a Llama-3-8B decode step
         if not args.no_lm_head:
             lm_head = measure_set({"lm_head": synth.LLAMA8B_LM_HEAD}, synth.gaussian_weights, 300, (1, 8), "lm_head")
+        # the MLP down projections the paper's efficiency table is measured on, at its batch sizes
+        if not args.no_qwen:
+            t_setup = time.perf_counter()
+            qw, _ = build_layers(synth.QWEN_DOWN_LAYERS, synth.gaussian_weights, 400, fmts, args.copies_mb, ams, torch)
+            print(f"# qwen setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr)
+            qwen_down = batch_sweep(qw, fmts, ams, torch, synth, n_launch, ws, batches=(1, 4, 16, 32))
+            del qw
+            gc.collect()
+            torch.cuda.empty_cache()
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(synth.LLAMA8B_LAYERS)
 
@@ -502,6 +512,8 @@ def main():
         # Llama-3-8B's vocabulary projection (128256 x 4096): a Linear large enough that the launch floor and the
         # epilogue stop mattering
         "lm_head": lm_head,
+        # the shapes of the paper's Table 3 (MLP down of Qwen3-4B, Qwen2.5-7B, Qwen3-32B) at batch 1, 4, 16, 32; columns as in batch_sweep
+        "qwen_down": qwen_down,
         "paper_context": "paper reports 2.8x / 3.2x decode speed-up over fp16 (FP5.33 / FP4.25) on an unnamed GPU of ~22 TFLOPS, 290 GB/s",
     }
     print(json.dumps(line))

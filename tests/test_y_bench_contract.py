@@ -15,7 +15,7 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     import sys
 
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "5", "--warmup", "2", "--no-cpu-baseline", "--no-70b", "--no-lm-head"],
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "5", "--warmup", "2", "--no-cpu-baseline", "--no-70b", "--no-lm-head", "--no-qwen"],
                        capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
@@ -33,5 +33,5 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert {(r["layer"], r["M"], r["fmt"]) for r in d["batch_sweep"]} == {(n, m, f) for n in ("gate_up", "down") for m in (1, 2, 4, 8, 16, 32)
                                                                        for f in ("fp5.33-e2m3", "fp4.25-e2m2")}
     assert all(r["us"] > 0 and (r["us_static_ws"] or 1) > 0 and r["speedup_vs_best_fp16"] > 0 for r in d["batch_sweep"])
-    assert d["llama70b"] is None and d["lm_head"] is None  # --no-70b --no-lm-head
+    assert d["llama70b"] is None and d["lm_head"] is None and d["qwen_down"] is None  # --no-70b --no-lm-head --no-qwen
     assert {(l["layer"], l["fmt"]) for l in d["layers"]} == {(n, f) for n in ("qkv", "o", "gate_up", "down") for f in ("fp5.33-e2m3", "fp4.25-e2m2")}

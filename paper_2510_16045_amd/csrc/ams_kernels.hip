@@ -1556,14 +1556,17 @@ ColumnPlan column_plan_for(int S, int lr, int fmt, int M, int64_t n_strips, int 
     bool qd = allow_qd && sg > 1 && gk == 1;
     int wpa = p.wps;
     if (qd) {
-      // the most wavefronts per strip (at least 7 of 8: measured, 14 wavefronts read as fast as 16) that get the same
-      // number of groups each, within 3 %
+      // the most wavefronts per strip, at least 7 of 8 of them, among which the groups divide within 20 %.  Measured
+      // on eleven shapes and four formats: a wavefront with a fifth more records than the average costs less than
+      // a side dword loaded with every record (each of a group's records is then read by another wavefront, and
+      // each loads the group's 256 bytes of side bits again: 2-14 % slower), while leaving more than an eighth of
+      // the wavefronts without records to make the groups divide costs more than it gains (up to 9 % slower)
       const int rcq = (rc + sg - 1) / sg * sg;
       const int groups = rcq / sg;
       qd = false;
       if ((size_t)M * (rcq * rec_k + 8) * 2 + parts <= (size_t)kLdsMaxBytes)
         for (int w = p.wps; w * 8 >= p.wps * 7 && w >= 1 && !qd; w--)
-          if (groups >= w && (groups + w - 1) / w * w * 100 <= groups * 103) qd = true, wpa = w;
+          if (groups >= w && (groups + w - 1) / w * w * 100 <= groups * 120) qd = true, wpa = w;
       if (qd) rc = rcq;
     }
     const int x_stride = rc * rec_k + 8;  // +8 halfs: consecutive rows start 16 bytes apart in the banks

@@ -177,3 +177,34 @@ def test_other_formats_without_side_groups_on_the_eight_wavefront_plans(fmt, ofm
         X = synth.activations(M, K, 781 + M)
         y = host16(ams.ams_linear(wp, sc, dev(X), N, fmt))
         check_linear(y[:, rows], O.linear(codes, o_scales, X, ofmt), f"{ofmt.name} N={N} K={K} M={M}")
+
+
+def test_random_shapes_with_many_strips_per_workgroup():
+    # seeded random problems with 7 to 16 strips per workgroup (lone wavefronts, two strips per wavefront, ragged last
+    # workgroups, odd record counts, unaligned rows), any format and batch: sampled strips against the oracle
+    rng = np.random.default_rng(451)
+    fmts = [(ams.FP533, O.FP533), (ams.FP425, O.FP425), (ams.FP45, O.FP45), (ams.FP433, O.FP433), (ams.FP6, O.FP6_E2M3),
+            (ams.FP5, O.FP5_E2M2), (ams.FP4, O.FP4_E2M1)]
+    seen = set()
+    for case in range(12):
+        fmt, ofmt = fmts[case % len(fmts)]
+        N = int(rng.integers(26000, 66000))
+        K = int(rng.integers(300, 150_000_000 // N))
+        if case % 3 == 0:
+            K = K // 8 * 8 + int(rng.integers(1, 8))  # rows that are not 16-byte aligned
+        M = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 17, 32]))
+        plan = ams.ams_linear_plan(fmt, M, N, K)
+        print(f"case {case}: {ofmt.name} N={N} K={K} M={M}: {plan}", flush=True)
+        kv = dict(x.split("=") for x in plan.split()[1:])
+        seen.add((kv["waves"], kv["strips_per_wave"], kv["waves_per_strip"]))
+        W = synth.gaussian_weights(N, K, 800 + case)
+        packed, scales = ams.ams_pack(fmt, W)
+        n_strips = -(-N // 16)
+        strips = sampled_strips(N, 331, tuple(range(n_strips - 18, n_strips)) + tuple(range(0, 18)))
+        rows = np.concatenate([np.arange(16 * t, min(N, 16 * t + 16)) for t in strips])
+        codes, o_scales, _ = O.ams_quantize(W[rows], ofmt)
+        X = synth.activations(M, K, 900 + case)
+        y = host16(ams.ams_linear(dev(packed), dev(scales), dev(X), N, fmt))
+        assert np.all(np.isfinite(y.astype(np.float32)))
+        check_linear(y[:, rows], O.linear(codes, o_scales, X, ofmt), f"case {case}: {ofmt.name} N={N} K={K} M={M}")
+    assert ("8", "2", "1") in seen and ("16", "1", "1") in seen  # two strips per wavefront; sixteen lone wavefronts

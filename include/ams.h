@@ -218,9 +218,10 @@ int ams_fp16_linear(const uint16_t* W, const uint16_t* X, uint16_t* Y, int M, in
 int ams_linear_workspace_bytes(int fmt, int M, int64_t N, int64_t K, size_t* bytes);
 /* Which kernel and launch shape ams_linear (with_workspace = 0) or ams_linear_ws (1) would use for
  * this problem (fmt = -1: the fp16 baseline), as a short text for logs and tests: "column ..." (the
- * packed formats), "gemv ...", "sweep ..." or "stream ..." (the baseline: batches up to 4 whose activations fit in
- * LDS, larger ones) followed by key=value pairs.  Host only,
- * launches nothing. */
+ * packed formats), "gemv ..." (the baseline at batches up to 4 whose activations fit in LDS), "sweep ..."
+ * or "stream ..." (the baseline otherwise), followed by key=value pairs (workgroups, strips per
+ * workgroup, slices of K, wavefronts, wavefronts per strip or strips per wavefront, phases of K, LDS
+ * bytes, records ahead).  Host only, launches nothing. */
 int ams_linear_plan(int fmt, int M, int64_t N, int64_t K, int with_workspace, char* text, size_t text_len);
 int ams_linear_ws(const void* W_packed, const uint16_t* scales, const uint16_t* X, uint16_t* Y, int M, int64_t N,
                   int64_t K, int fmt, void* workspace, size_t workspace_bytes, void* stream);

@@ -298,6 +298,9 @@ def main():
         sys.exit(2)
     import torch
 
+    import __graft_entry__
+
+    __graft_entry__.ensure_built()  # loads what is built; a tree with no library gets one built first
     import paper_2510_16045_amd as ams
     from paper_2510_16045_amd import synth
 

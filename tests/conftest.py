@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only a tree with none gets one built here
+    import __graft_entry__
+
+    __graft_entry__.ensure_built()
 
 
 def pytest_collection_modifyitems(config, items):

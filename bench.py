@@ -501,6 +501,8 @@ def main():
             if args.layers == "8b" else f"{args.layers} layer set, M=1, both formats",
             "linears_per_step": len(shapes) * len(fmts), "packed_bytes_per_step": step_bytes,
             "hbm_peak_GBps": HBM_PEAK_GBPS, "hbm_frac": round(value / HBM_PEAK_GBPS, 4),
+            "fp16_baseline": "in-build ams_fp16_linear: a GEMV on the VALU at M <= 4 (rows dealt to wavefronts), the MFMA kernels above; "
+                             "speedup_vs_best_fp16 takes the fastest of it, its workspace variant and the library GEMM",
             "launch_floor_us": round(launch_floor, 3), "clock_ramp_s": CLOCK_RAMP_S, "entry_point": "ams_linear_ws" if args.workspace else "ams_linear",
         },
         "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
